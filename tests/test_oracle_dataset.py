@@ -1,0 +1,84 @@
+"""Pins of the dataset-state oracle: a step-by-step simulation of data-parallel
+consumption (independent of the oracle's index formula) and the consistency
+requirements the paper states (sections 1 and 2.2: every sample exactly once per
+epoch, consumption order unchanged by a re-partitioning, constant global batch)."""
+import numpy as np
+import pytest
+
+import synth
+from oracle import dataset as ods
+
+
+def simulate(parts, B, start_cursors=None, steps=None):
+    """Run the data-parallel loop: at each step replica j takes its next B/D entries.
+    Returns the samples in the order the job as a whole consumes them (step-major,
+    replica-minor) and the cursors afterwards."""
+    D = len(parts)
+    b = B // D
+    cur = list(start_cursors) if start_cursors is not None else [0] * D
+    out = []
+    k = 0
+    while (steps is None or k < steps) and any(cur[j] < len(parts[j]) for j in range(D)):
+        for j in range(D):
+            take = parts[j][cur[j]:cur[j] + b]
+            out.extend(int(x) for x in take)
+            cur[j] += len(take)
+        k += 1
+    return out, cur
+
+
+@pytest.mark.parametrize("n,B,D", [(48, 12, 3), (50, 12, 3), (53, 12, 4), (7, 12, 6), (100, 24, 6), (101, 24, 4), (0, 12, 2)])
+def test_partition_consumes_global_order(n, B, D):
+    G = synth.epoch_order(n, 7) if n else np.zeros(0, dtype=np.uint64)
+    parts = ods.partition(G, B, D)
+    order, cur = simulate(parts, B)
+    assert order == [int(x) for x in G]                       # exactly once, in the global order
+    assert cur == [len(p) for p in parts]
+    assert np.array_equal(ods.global_order(parts, B), G)
+
+
+@pytest.mark.parametrize("n,B,D,D2,s", [(100, 24, 6, 4, 2), (101, 24, 4, 6, 3), (53, 12, 2, 3, 0), (53, 12, 3, 1, 4),
+                                        (53, 12, 3, 4, 5), (96, 24, 6, 4, 4), (200, 24, 6, 4, 9)])
+def test_repartition_continues_the_same_order(n, B, D, D2, s):
+    G = synth.epoch_order(n, 3)
+    parts = ods.partition(G, B, D)
+    before, cur = simulate(parts, B, steps=s)
+    assert cur == ods.cursors_after(n, B, D, s)
+    new_parts, new_cur = ods.repartition(parts, cur, B, D2)
+    after, _ = simulate(new_parts, B, start_cursors=new_cur)
+    assert before + after == [int(x) for x in G]              # nothing lost, repeated or reordered
+    consumed_new = sorted(int(x) for j in range(D2) for x in new_parts[j][:new_cur[j]])
+    assert consumed_new == sorted(before)                     # consumed set carried over
+    assert sorted(int(x) for p in new_parts for x in p) == list(range(n))
+
+
+def test_same_degree_is_identity_and_round_trip():
+    G = synth.epoch_order(1000, 9)
+    parts = ods.partition(G, 48, 6)
+    cur = ods.cursors_after(1000, 48, 6, 11)
+    same, cur_same = ods.repartition(parts, cur, 48, 6)
+    assert all(np.array_equal(a, b) for a, b in zip(parts, same)) and cur_same == cur
+    four, cur4 = ods.repartition(parts, cur, 48, 4)
+    back, cur_back = ods.repartition(four, cur4, 48, 6)
+    assert all(np.array_equal(a, b) for a, b in zip(parts, back)) and cur_back == cur
+
+
+def test_ragged_tail_of_the_benchmark_shape():
+    """B = 768, D 6 -> 4 with a tail of 256 samples: the tail lands on replicas 0 and 1 in
+    both layouts, as 128 + 128 and as 192 + 64."""
+    n, B = 768 * 5 + 256, 768
+    G = synth.epoch_order(n, 6)
+    p6, p4 = ods.partition(G, B, 6), ods.partition(G, B, 4)
+    assert [len(p) for p in p6] == [5 * 128 + 128, 5 * 128 + 128, 640, 640, 640, 640]
+    assert [len(p) for p in p4] == [5 * 192 + 192, 5 * 192 + 64, 960, 960]
+
+
+def test_inconsistent_cursors_are_rejected():
+    G = synth.epoch_order(100, 1)
+    parts = ods.partition(G, 24, 4)
+    with pytest.raises(ValueError):
+        ods.repartition(parts, [6, 6, 6, 5], 24, 2)
+    with pytest.raises(ValueError):
+        ods.repartition(parts, [7, 7, 7, 7], 24, 2)
+    with pytest.raises(ValueError):
+        ods.partition(G, 25, 4)

@@ -1,0 +1,234 @@
+#!/usr/bin/env python3
+"""Benchmark of the resharding hot path on one MI355X.
+
+A step is one whole reconfiguration of the workload's job state: tpx_plan (host: split / re-partition /
+merge into a copy list, tiled), the upload of the tile table, and tpx_execute (one kernel launch that
+moves all state).  Source and destination rank buffers are resident in HBM before the timed region.
+
+Prints one JSON line.  `value` is state bytes read + written per second of step time; `roofline`
+describes the copy kernel alone, timed with HIP events on the launch stream; `cpu_baseline` is the
+CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+GPT_STATE = (2, 4, 4, 4)
+WORKLOADS = {
+    # name: (model kwargs, src, dst, synth mix name, seed)
+    "tiny_2L_h256_(2,1,1)->(4,2,1)": (dict(n_layers=2, hidden=256, n_heads=4, ffn=1024, vocab_true=1024, max_pos=1024,
+                                           state_elem_bytes=(4, 4, 4)), dict(T=2, P=1, D=1), dict(T=4, P=2, D=1), "tiny", 1),
+    "gpt1.3b_(4,2,1)->(2,4,1)": (dict(n_layers=24, hidden=2048, n_heads=16, ffn=8192, vocab_true=50304,
+                                      state_elem_bytes=GPT_STATE), dict(T=4, P=2, D=1), dict(T=2, P=4, D=1), "gpt", 2),
+    "gpt2.7b_(4,4,2)->(2,4,1)": (dict(n_layers=32, hidden=2560, n_heads=32, ffn=10240, vocab_true=50304,
+                                      state_elem_bytes=GPT_STATE), dict(T=4, P=4, D=2),
+                                 dict(T=2, P=4, D=1, stage_first_layer=(0, 7, 16, 25, 32)), "gpt", 3),
+    "gpt6.7b_(8,1,1)->(1,8,1)": (dict(n_layers=32, hidden=4096, n_heads=32, ffn=16384, vocab_true=50304,
+                                      state_elem_bytes=GPT_STATE), dict(T=8, P=1, D=1), dict(T=1, P=8, D=1), "gpt", 4),
+    "gpt_h3072_T3->T4_padded_vocab": (dict(n_layers=24, hidden=3072, n_heads=24, ffn=12288, vocab_true=50257,
+                                           vocab_divisor=128, state_elem_bytes=GPT_STATE),
+                                      dict(T=3, P=1, D=1), dict(T=4, P=1, D=1), "gpt", 5),
+}
+DEFAULT_WORKLOAD = "gpt6.7b_(8,1,1)->(1,8,1)"
+
+# HBM bytes per launch of the copy kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE runs, or None.
+MEASURED_TRAFFIC = {}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(WORKLOADS))
+    ap.add_argument("--cpu-layers", type=int, default=2, help="layers in the CPU oracle's sample (0 = skip)")
+    ap.add_argument("--tile-bytes", type=int, default=0)
+    ap.add_argument("--variant", type=int, default=-1)
+    ap.add_argument("--no-probe", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (all partitions of both configurations live in one "
+              "GPU's HBM); --gpus must be 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2312_05181_amd as tpx
+    import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    torch.cuda.set_device(0)
+    if args.tile_bytes:
+        tpx.tpx_set_option("tile_bytes", args.tile_bytes)
+    if args.variant >= 0:
+        tpx.tpx_set_option("variant", args.variant)
+
+    model, src, dst, mixname, seed = WORKLOADS[args.workload]
+    mix = synth.MIX_TINY if mixname == "tiny" else synth.MIX_GPT
+    plan = tpx.tpx_plan(model, src, dst)
+    stats = plan.stats()
+    n_src, n_dst = plan.num_buffers(0), plan.num_buffers(1)
+
+    def descs_of(side, r):
+        return [synth.ShardDesc(e.tensor_id, e.kind, e.elem_bytes, e.offset, tuple(e.full_shape[:e.ndim]),
+                                tuple(e.lo[:e.ndim]), tuple(e.hi[:e.ndim]), tuple(e.perm[:e.ndim]))
+                for e in plan.manifest(side, r)]
+
+    t_setup = time.time()
+    src_bufs, dst_bufs = [], []
+    for r in range(n_src):
+        b = torch.empty(plan.buffer_bytes(0, r), dtype=torch.uint8, device="cuda")
+        synth.fill_buffer(b, descs_of(0, r), seed, mix)
+        src_bufs.append(b)
+    for r in range(n_dst):
+        dst_bufs.append(torch.zeros(plan.buffer_bytes(1, r), dtype=torch.uint8, device="cuda"))
+    ws = torch.empty(plan.workspace_bytes(), dtype=torch.uint8, device="cuda")
+    src_ptrs = [b.data_ptr() for b in src_bufs]
+    dst_ptrs = [b.data_ptr() for b in dst_bufs]
+    stream = torch.cuda.current_stream().cuda_stream
+    torch.cuda.synchronize()
+    setup_s = time.time() - t_setup
+
+    state_bytes = stats["bytes_read"] + stats["bytes_written"]
+
+    def step(ev0=None, ev1=None):
+        p = tpx.tpx_plan(model, src, dst)           # a1-a5: host planner
+        p.prepare(ws.data_ptr(), stream)            # tile table -> HBM
+        if ev0 is not None:
+            ev0.record()
+        p.execute(src_ptrs, dst_ptrs, ws.data_ptr(), stream)   # a6: one launch
+        if ev1 is not None:
+            ev1.record()
+        return p
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    plans = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        plans.append(step(*evs[i]))
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kernel_ms = [a.elapsed_time(b) for a, b in evs]
+    kernel_ms_avg = sum(kernel_ms) / len(kernel_ms)
+    plan_ms = sum(p.stats()["plan_ns"] for p in plans) / len(plans) / 1e6
+    del plans
+
+    achieved = state_bytes / (kernel_ms_avg * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC.get(args.workload),
+                "kernel": "tpx_execute_tiles", "kernel_ms_avg": round(kernel_ms_avg, 4),
+                "kernel_ms_min": round(min(kernel_ms), 4), "algorithmic_bytes_per_launch": state_bytes}
+
+    probe = None
+    if not args.no_probe:
+        n = min(8 << 30, min(b.numel() for b in src_bufs if b.numel()) // 16 * 16, dst_bufs[0].numel() // 16 * 16)
+        a, b = src_bufs[0], dst_bufs[0]
+        for _ in range(2):
+            tpx.tpx_probe_copy(b.data_ptr(), a.data_ptr(), n, stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            tpx.tpx_probe_copy(b.data_ptr(), a.data_ptr(), n, stream)
+        e1.record()
+        torch.cuda.synchronize()
+        probe = round(2 * n * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+
+    cpu = None
+    if args.cpu_layers > 0:
+        cpu = cpu_baseline(args, model, src, dst, plan, src_bufs, dst_bufs, src_ptrs, dst_ptrs, ws, stream)
+
+    out = {
+        "metric": "reshard_GBps_state_bytes_read_plus_written",
+        "value": round(state_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": args.workload, "state_bytes_read": stats["bytes_read"],
+                   "state_bytes_written": stats["bytes_written"], "n_boxes": stats["n_boxes"],
+                   "n_tiles": stats["n_tiles"], "src_ranks": n_src, "dst_ranks": n_dst},
+        "pct_of_hbm_peak": round(100 * achieved / HBM_PEAK_GBPS, 2),
+        "ms_per_reconfig": {"plan_host": round(plan_ms, 4), "kernel": round(kernel_ms_avg, 4),
+                            "whole_step": round(ms_per_step, 4)},
+        "copy_probe_GBps": probe,
+        "setup_s": round(setup_s, 1),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def cpu_baseline(args, model, src, dst, plan, src_bufs, dst_bufs, src_ptrs, dst_ptrs, ws, stream):
+    """Time the CPU oracle (numpy: paste the old shards into the full tensor, slice it anew) on the state
+    tensors of the first `--cpu-layers` layers, threaded over tensors; check the GPU result against it."""
+    import numpy as np
+    import torch
+    from concurrent.futures import ThreadPoolExecutor
+
+    from oracle import reshard as oreshard
+    from oracle import spec
+
+    om = spec.Model(model["n_layers"], model["hidden"], model["n_heads"], model["ffn"], model["vocab_true"],
+                    model.get("max_pos", 1024), model.get("vocab_divisor", 0), tuple(model["state_elem_bytes"]))
+    osrc = spec.Parallel(src["T"], src["P"], src["D"], src.get("stage_first_layer"))
+    odst = spec.Parallel(dst["T"], dst["P"], dst["D"], dst.get("stage_first_layer"))
+    src_lay, dst_lay = oreshard.Layout(om, osrc), oreshard.Layout(om, odst)
+    layers = min(args.cpu_layers, om.n_layers)
+    work = [(4 + l * 12 + k, kind) for l in range(layers) for k in range(12) for kind in range(len(om.state_elem_bytes))]
+    # fetch the sample's source shards to host memory first (not timed)
+    cache = {}
+    for tid, kind in work:
+        for rank, e in src_lay.by_tensor[(tid, kind)]:
+            n = int(np.prod([h - l for l, h in zip(e.lo, e.hi)])) * e.elem_bytes
+            cache[(rank, e.offset)] = src_bufs[rank][e.offset:e.offset + n].cpu().numpy()
+
+    def read(rank, off, n):
+        return cache[(rank, off)]
+
+    threads = max(1, min(16, os.cpu_count() or 1))
+    results = {}
+
+    def one(tk):
+        results[tk] = oreshard.reshard_tensor(om, osrc, odst, src_lay, dst_lay, tk[0], tk[1], read)
+
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(threads) as ex:
+        list(ex.map(one, work))
+    secs = time.perf_counter() - t0
+    moved = 0
+    plan.execute(src_ptrs, dst_ptrs, ws.data_ptr(), stream)
+    torch.cuda.synchronize()
+    ok = True
+    for tk, outs in results.items():
+        for rank, e, block in outs:
+            moved += 2 * block.nbytes
+            have = dst_bufs[rank][e.offset:e.offset + block.nbytes].cpu().numpy()
+            ok = ok and bool(np.array_equal(have, block.reshape(-1).view(np.uint8)))
+    return {"value": round(moved / secs / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": f"all state tensors of the first {layers} of {om.n_layers} layers "
+                      f"({moved / 2e9:.2f} GB read + the same written), numpy, {threads} threads over tensors",
+            "seconds": round(secs, 2), "gpu_matches_oracle_on_sample": ok}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,213 @@
+/*
+ * tpx - re-partitioning of a training job's state between two multi-dimensional
+ * parallelism configurations, on one MI355X (gfx950).
+ *
+ * The job state is a parallelizable tensor collection PTC = (T, sigma, phi, alpha)
+ * (paper section 4.1, equation 1): state tensors T, a slicing function sigma
+ * (tensor parallelism), a partitioning function phi (pipeline stages and
+ * data-parallel replicas) and an allocation function alpha (sub-collection ->
+ * device).  Given the current PTC and a new PTC' over the same tensors, a
+ * reconfiguration plan made of split, re-partition (move) and merge operations
+ * turns the state of the one into the state of the other (section 4.2,
+ * algorithm 1), and a state transformer applies it (section 5.1, step 4).
+ *
+ * Here every "device" of either configuration is one flat buffer in the HBM of a
+ * single GPU: rank (t, p, d) of a configuration (T, P, D) is buffer index
+ * t + T*(d + D*p).  tpx_plan() computes the plan on the host; tpx_execute()
+ * applies the whole plan with one kernel launch.
+ *
+ * Conventions for every call
+ *   - pointers are HOST pointers unless the comment says DEVICE;
+ *   - the caller owns all device memory (rank buffers and the workspace); the
+ *     library owns only the host-side plan object, released by tpx_free();
+ *   - a call returns TPX_OK or a negative tpx_status, never throws or aborts;
+ *     out-parameters are untouched on error; tpx_last_error() returns a
+ *     thread-local description of the last failure on the calling thread.
+ */
+#ifndef TPX_H
+#define TPX_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tpx_plan_s tpx_plan_t; /* opaque */
+
+typedef enum {
+  TPX_OK = 0,
+  TPX_ERR_INVALID_ARG = -1,   /* NULL pointer, zero degree, unsupported size, bad index */
+  TPX_ERR_INDIVISIBLE = -2,   /* heads / hidden / ffn / vocabulary / layers / batch not divisible */
+  TPX_ERR_BAD_STAGE_MAP = -3, /* stage boundaries not ascending from 0 to n_layers */
+  TPX_ERR_OOM = -4,           /* host allocation failed */
+  TPX_ERR_HIP = -5,           /* a HIP runtime call failed (message has the HIP error) */
+  TPX_ERR_CURSOR = -7,        /* dataset cursors are not those of a whole number of steps */
+  TPX_ERR_UNRECOVERABLE = -8  /* some state has no surviving source holder */
+} tpx_status;
+
+#define TPX_MAX_RANKS 128u    /* buffers per side */
+#define TPX_SIDE_SRC 0
+#define TPX_SIDE_DST 1
+
+/* ---- the tensor collection T: a GPT-style model and its state mix ------------------- */
+#define TPX_MODEL_TIED_HEAD 1u /* last stage also holds the word embeddings when P > 1 */
+
+typedef struct {
+  uint32_t n_layers, hidden, n_heads, ffn, vocab_true, max_pos;
+  uint32_t vocab_divisor;       /* 0: vocab_true must divide by T; else rows are padded to a multiple of divisor*T */
+  uint32_t n_state_kinds;       /* 1..4 state tensors per parameter (weight, master copy, Adam m, Adam v, ...) */
+  uint8_t  state_elem_bytes[4]; /* element size of each state kind: 1, 2, 4 or 8 */
+  uint32_t flags;               /* TPX_MODEL_* */
+} tpx_model;
+
+/* ---- sigma, phi, alpha of one configuration ------------------------------------------ */
+typedef struct {
+  uint32_t T, P, D;                  /* tensor-, pipeline-, data-parallel degree */
+  const uint32_t* stage_first_layer; /* phi: P+1 ascending layer boundaries, [0]=0, [P]=n_layers; NULL = n_layers/P each */
+  uint32_t qkv_layout;               /* sigma of the fused QKV tensors: 0 head-major [a,3,d,*], 1 qkv-major [3,a,d,*] */
+  uint32_t w_transposed;             /* 1: 2-D weights are stored [in, out] instead of [out, in] */
+  const uint8_t* rank_alive;         /* T*P*D bytes, 0 = this rank's buffer is lost (section 5.3); NULL = all alive.
+                                        Only meaningful for the source configuration. */
+} tpx_parallel;
+
+/* One stored sub-tensor of a rank buffer ("/<rank>/<module path>/<param>", section 5.2).
+ * The full tensor has `ndim` canonical axes; the block covers [lo, hi) on each and is stored
+ * dense row-major with stored axis i = canonical axis perm[i]. */
+typedef struct {
+  uint32_t tensor_id;  /* 0 word emb, 1 pos emb, 2/3 final LayerNorm w/b, 4 + 12*layer + k for the k-th per-layer tensor */
+  uint32_t kind;       /* state kind index */
+  uint32_t elem_bytes;
+  uint32_t ndim;
+  uint32_t name;       /* index into the 16 parameter names, see tpx_param_name() */
+  int32_t  layer;      /* -1 for global tensors */
+  uint64_t offset;     /* byte offset inside the rank buffer, multiple of 256 */
+  uint64_t nbytes;
+  uint64_t full_shape[4], lo[4], hi[4];
+  uint32_t perm[4];
+} tpx_entry;
+
+/* One move of the plan (algorithm 1: move(w, r_w, r') together with the split that produced w
+ * and w's place in the merge).  Byte j of unit (i_0, .., i_{ndim-1}), 0 <= i_k < extent[k],
+ * 0 <= j < run_bytes, goes from  src_off + sum_k i_k*src_stride[k] + j  of buffer src_rank
+ * to  dst_off + sum_k i_k*dst_stride[k] + j  of buffer dst_rank.  TPX_BOX_FILL writes zeros and has
+ * no source.  TPX_BOX_TRANSPOSE moves single elements (run_bytes == elem_bytes): no axis is
+ * contiguous on both sides.  Axes are ordered by descending destination stride. */
+#define TPX_BOX_COPY 0u
+#define TPX_BOX_FILL 1u
+#define TPX_BOX_TRANSPOSE 2u
+typedef struct {
+  uint32_t kind;
+  uint32_t src_rank, dst_rank;
+  uint32_t ndim;          /* number of outer axes used, 0..4 */
+  uint32_t elem_bytes;
+  uint32_t tensor_id;     /* of the first tensor it covers (boxes of neighbouring tensors may be merged) */
+  uint64_t src_off, dst_off;
+  uint64_t run_bytes;
+  uint64_t extent[4];
+  uint64_t src_stride[4]; /* bytes */
+  uint64_t dst_stride[4]; /* bytes */
+} tpx_box;
+
+/* One unit of GPU work: a bounded piece of one box, executed by one workgroup.  The device-side tile
+ * table is an array of exactly this struct.  Unit (i, j), 0 <= i < nrows, 0 <= j < run_units, of
+ * 1 << unit_log2 bytes goes from  src_off + i*src_pitch + j*src_step  to
+ * dst_off + i*dst_pitch + j*dst_step. */
+#define TPX_TILE_COPY 0u      /* src_step == dst_step == unit: rows are contiguous on both sides */
+#define TPX_TILE_FILL 1u      /* like COPY, zeros instead of a source */
+#define TPX_TILE_TRANSPOSE 2u /* unit = element; rows are contiguous on the source (src_step == unit),
+                                 columns on the destination (dst_pitch == unit); staged through LDS */
+#define TPX_TILE_GATHER 3u    /* unit = element; arbitrary steps (degenerate transposes) */
+typedef struct {
+  uint64_t src_off, dst_off;  /* bytes, inside the rank buffers */
+  uint64_t src_pitch, dst_pitch;
+  uint64_t src_step, dst_step;
+  uint32_t run_units;
+  uint32_t nrows;
+  uint16_t src_rank, dst_rank;
+  uint8_t  kind;
+  uint8_t  unit_log2;         /* 4 (16-byte vectors) when offsets, pitches and run length allow, else smaller */
+  uint8_t  pad_[2];
+} tpx_tile;                   /* 64 bytes */
+
+typedef struct {
+  uint64_t n_pieces;          /* sub-tensor pieces produced by the split step */
+  uint64_t n_boxes;           /* moves after merging neighbours */
+  uint64_t n_tiles;
+  uint64_t bytes_read;        /* source bytes read (= bytes_written - bytes_fill) */
+  uint64_t bytes_written;     /* destination bytes written (= all destination tensor bytes) */
+  uint64_t bytes_fill;        /* zero-filled destination bytes (vocabulary padding growth) */
+  uint64_t bytes_cross_rank;  /* bytes whose source buffer index differs from the destination's */
+  uint64_t plan_ns;           /* host time spent in tpx_plan */
+} tpx_stats_t;
+
+/* Plan the transformation of the model state of `model` from configuration src to dst (algorithm 1).
+ * Errors: INVALID_ARG (NULL, zero degree, > TPX_MAX_RANKS ranks, element size not 1/2/4/8),
+ * INDIVISIBLE, BAD_STAGE_MAP, UNRECOVERABLE (src->rank_alive leaves a tensor without holder), OOM. */
+tpx_status tpx_plan(const tpx_model* model, const tpx_parallel* src, const tpx_parallel* dst, tpx_plan_t** out);
+
+/* Plan the transformation of the dataset state (sections 2.2 and 5.2): per-replica sample-index arrays
+ * of one epoch are re-partitioned from D_src to D_dst replicas with the global batch unchanged, so that
+ * the job consumes the same samples in the same order.  Replica j's index array holds, for every step k,
+ * entries [k*B + j*b, k*B + (j+1)*b) of the global order (b = B/D), clipped to n_samples; buffer j of a
+ * side is that array (index_elem_bytes per entry: 8 for sample ids, 16 for (offset, length) pairs).
+ * src_cursors[j] = consumed entries of source partition j; dst_cursors (D_dst entries, written on success)
+ * receives the equivalent positions.  Errors: INVALID_ARG, INDIVISIBLE (B % D), CURSOR. */
+tpx_status tpx_plan_dataset(uint64_t n_samples, uint32_t global_batch, uint32_t index_elem_bytes,
+                            uint32_t D_src, uint32_t D_dst, const uint64_t* src_cursors,
+                            uint64_t* dst_cursors, tpx_plan_t** out);
+
+/* Queries (cheap, host only). side: TPX_SIDE_SRC / TPX_SIDE_DST. Out-of-range indices give 0 / INVALID_ARG. */
+uint32_t   tpx_num_buffers(const tpx_plan_t*, int side);
+uint64_t   tpx_buffer_bytes(const tpx_plan_t*, int side, uint32_t rank);
+uint32_t   tpx_num_entries(const tpx_plan_t*, int side, uint32_t rank);
+tpx_status tpx_manifest(const tpx_plan_t*, int side, uint32_t rank, uint32_t i, tpx_entry* out);
+const char* tpx_param_name(uint32_t name); /* static string, NULL if out of range */
+tpx_status tpx_stats(const tpx_plan_t*, tpx_stats_t* out);
+uint64_t   tpx_num_boxes(const tpx_plan_t*);
+tpx_status tpx_get_box(const tpx_plan_t*, uint64_t i, tpx_box* out);
+uint64_t   tpx_num_tiles(const tpx_plan_t*);
+tpx_status tpx_get_tile(const tpx_plan_t*, uint64_t i, tpx_tile* out);
+
+/* DEVICE bytes tpx_execute needs in `workspace` (the tile table). */
+uint64_t   tpx_workspace_bytes(const tpx_plan_t*);
+
+/* Apply the plan (section 5.1, step 4): one kernel launch on `hip_stream` (a hipStream_t, NULL = the
+ * default stream).  src_bufs / dst_bufs are HOST arrays of DEVICE pointers, one per rank of the side,
+ * each at least tpx_buffer_bytes() long and 16-byte aligned (256 recommended); entries of lost source
+ * ranks may be NULL.  workspace is a DEVICE pointer to tpx_workspace_bytes() bytes, 64-byte aligned.
+ * Every destination tensor byte is written exactly once; bytes between tensors are left untouched;
+ * sources are only read and must not overlap destinations.  The call does not wait for the kernel.
+ * The first call with a given workspace copies the tile table into it and waits for that copy;
+ * later calls with the same workspace reuse it, so the caller must not modify the workspace in
+ * between (see tpx_workspace_forget()).  A plan may be executed any number of times; concurrent
+ * executions of one plan must use the same, already filled workspace.
+ * Errors: INVALID_ARG (NULL where a pointer is needed, misaligned pointer), HIP. */
+tpx_status tpx_execute(tpx_plan_t*, const void* const* src_bufs, void* const* dst_bufs,
+                       void* workspace, void* hip_stream);
+
+/* Optional: copy the tile table into `workspace` now (and wait for the copy), so that a following
+ * tpx_execute with the same workspace only launches the kernel.  Errors: INVALID_ARG, HIP. */
+tpx_status tpx_prepare(tpx_plan_t*, void* workspace, void* hip_stream);
+
+/* Forget which workspace holds the tile table (call after overwriting or freeing it). */
+void tpx_workspace_forget(tpx_plan_t*);
+
+void tpx_free(tpx_plan_t*);
+const char* tpx_last_error(void);
+
+/* Global tuning knobs, read by later tpx_plan / tpx_execute calls on any thread:
+ *   "tile_bytes"  upper bound of bytes per tile (power of two, 4096 .. 4194304; default 262144)
+ *   "variant"     kernel variant (0 = default; others are documented in the kernel source)
+ * Errors: INVALID_ARG for an unknown key or a value out of range. */
+tpx_status tpx_set_option(const char* key, uint64_t value);
+
+/* Plain device-to-device copy of nbytes (multiple of 16, DEVICE pointers 16-byte aligned) by a simple
+ * grid-stride kernel on hip_stream: the yardstick for achievable HBM copy bandwidth and the
+ * calibration point for hardware traffic counters. */
+tpx_status tpx_probe_copy(void* dst, const void* src, uint64_t nbytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TPX_H */

@@ -46,7 +46,7 @@ def global_order(parts: list, B: int) -> np.ndarray:
     D = len(parts)
     n = sum(len(p) for p in parts)
     own = _owner(n, B, D)
-    G = np.empty(n, dtype=parts[0].dtype)
+    G = np.empty((n,) + parts[0].shape[1:], dtype=parts[0].dtype)   # an entry may be a row (e.g. an (offset, length) pair)
     for j in range(D):
         if np.count_nonzero(own == j) != len(parts[j]):
             raise ValueError("partition sizes are not those of a consistent partitioning")

@@ -52,7 +52,7 @@ def holders(model: Model, par: Parallel, tid: int, kind: int):
     return out
 
 
-class _Layout:
+class Layout:
     """All rank manifests of one configuration, indexed by (tensor id, kind)."""
 
     def __init__(self, model: Model, par: Parallel):
@@ -65,7 +65,7 @@ class _Layout:
                 self.by_tensor.setdefault((e.tensor_id, e.kind), []).append((rank, e))
 
 
-def full_tensor(model: Model, par: Parallel, lay: _Layout, tid: int, kind: int,
+def full_tensor(model: Model, par: Parallel, lay: Layout, tid: int, kind: int,
                 read: Callable[[int, int, int], np.ndarray]) -> np.ndarray:
     """Reassemble one full state tensor (canonical axis order) from the shards of `par`.
 
@@ -103,7 +103,7 @@ def _numel(e) -> int:
     return n
 
 
-def reshard_tensor(model: Model, src: Parallel, dst: Parallel, src_lay: _Layout, dst_lay: _Layout,
+def reshard_tensor(model: Model, src: Parallel, dst: Parallel, src_lay: Layout, dst_lay: Layout,
                    tid: int, kind: int, read) -> list:
     """[(dst rank, entry, stored block)] for every destination holder of one state tensor."""
     full = full_tensor(model, src, src_lay, tid, kind, read)
@@ -130,7 +130,7 @@ def reshard(model: Model, src: Parallel, dst: Parallel, src_bufs: list,
     work to some parameter tensors (all state kinds); other bytes stay POISON."""
     spec.check(model, src)
     spec.check(model, dst)
-    src_lay, dst_lay = _Layout(model, src), _Layout(model, dst)
+    src_lay, dst_lay = Layout(model, src), Layout(model, dst)
     if len(src_bufs) != src.n_ranks:
         raise ValueError("need one source buffer per source rank")
     for b, n in zip(src_bufs, src_lay.sizes):

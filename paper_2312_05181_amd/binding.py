@@ -1,0 +1,247 @@
+"""ctypes binding of libtpx: argument marshalling only.  Every step of the path runs
+inside the library (host planner in C++, execution in HIP kernels); nothing here
+computes, and there is no fallback: if the library cannot be loaded, importing
+this module fails."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtpx.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2312_05181_amd.build` "
+                      "(there is no CPU fallback)")
+_lib = C.CDLL(LIB_PATH)
+
+TPX_OK = 0
+TPX_ERR_INVALID_ARG, TPX_ERR_INDIVISIBLE, TPX_ERR_BAD_STAGE_MAP, TPX_ERR_OOM, TPX_ERR_HIP = -1, -2, -3, -4, -5
+TPX_ERR_CURSOR, TPX_ERR_UNRECOVERABLE = -7, -8
+TPX_MAX_RANKS = 128
+SIDE_SRC, SIDE_DST = 0, 1
+MODEL_TIED_HEAD = 1
+BOX_COPY, BOX_FILL, BOX_TRANSPOSE = 0, 1, 2
+TILE_COPY, TILE_FILL, TILE_TRANSPOSE, TILE_GATHER = 0, 1, 2, 3
+
+
+class TpxError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"tpx status {status}: {message}")
+        self.status = status
+
+
+class tpx_model(C.Structure):
+    _fields_ = [("n_layers", C.c_uint32), ("hidden", C.c_uint32), ("n_heads", C.c_uint32), ("ffn", C.c_uint32),
+                ("vocab_true", C.c_uint32), ("max_pos", C.c_uint32), ("vocab_divisor", C.c_uint32),
+                ("n_state_kinds", C.c_uint32), ("state_elem_bytes", C.c_uint8 * 4), ("flags", C.c_uint32)]
+
+
+class tpx_parallel(C.Structure):
+    _fields_ = [("T", C.c_uint32), ("P", C.c_uint32), ("D", C.c_uint32),
+                ("stage_first_layer", C.POINTER(C.c_uint32)), ("qkv_layout", C.c_uint32),
+                ("w_transposed", C.c_uint32), ("rank_alive", C.POINTER(C.c_uint8))]
+
+
+class tpx_entry(C.Structure):
+    _fields_ = [("tensor_id", C.c_uint32), ("kind", C.c_uint32), ("elem_bytes", C.c_uint32), ("ndim", C.c_uint32),
+                ("name", C.c_uint32), ("layer", C.c_int32), ("offset", C.c_uint64), ("nbytes", C.c_uint64),
+                ("full_shape", C.c_uint64 * 4), ("lo", C.c_uint64 * 4), ("hi", C.c_uint64 * 4),
+                ("perm", C.c_uint32 * 4)]
+
+
+class tpx_box(C.Structure):
+    _fields_ = [("kind", C.c_uint32), ("src_rank", C.c_uint32), ("dst_rank", C.c_uint32), ("ndim", C.c_uint32),
+                ("elem_bytes", C.c_uint32), ("tensor_id", C.c_uint32), ("src_off", C.c_uint64),
+                ("dst_off", C.c_uint64), ("run_bytes", C.c_uint64), ("extent", C.c_uint64 * 4),
+                ("src_stride", C.c_uint64 * 4), ("dst_stride", C.c_uint64 * 4)]
+
+
+class tpx_tile(C.Structure):
+    _fields_ = [("src_off", C.c_uint64), ("dst_off", C.c_uint64), ("src_pitch", C.c_uint64),
+                ("dst_pitch", C.c_uint64), ("src_step", C.c_uint64), ("dst_step", C.c_uint64),
+                ("run_units", C.c_uint32), ("nrows", C.c_uint32), ("src_rank", C.c_uint16),
+                ("dst_rank", C.c_uint16), ("kind", C.c_uint8), ("unit_log2", C.c_uint8), ("pad_", C.c_uint8 * 2)]
+
+
+class tpx_stats_t(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in ("n_pieces", "n_boxes", "n_tiles", "bytes_read", "bytes_written",
+                                          "bytes_fill", "bytes_cross_rank", "plan_ns")]
+
+
+assert C.sizeof(tpx_tile) == 64
+
+_P = C.c_void_p
+_sigs = {
+    "tpx_plan": (C.c_int, [C.POINTER(tpx_model), C.POINTER(tpx_parallel), C.POINTER(tpx_parallel), C.POINTER(_P)]),
+    "tpx_plan_dataset": (C.c_int, [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32,
+                                   C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(_P)]),
+    "tpx_num_buffers": (C.c_uint32, [_P, C.c_int]),
+    "tpx_buffer_bytes": (C.c_uint64, [_P, C.c_int, C.c_uint32]),
+    "tpx_num_entries": (C.c_uint32, [_P, C.c_int, C.c_uint32]),
+    "tpx_manifest": (C.c_int, [_P, C.c_int, C.c_uint32, C.c_uint32, C.POINTER(tpx_entry)]),
+    "tpx_param_name": (C.c_char_p, [C.c_uint32]),
+    "tpx_stats": (C.c_int, [_P, C.POINTER(tpx_stats_t)]),
+    "tpx_num_boxes": (C.c_uint64, [_P]),
+    "tpx_get_box": (C.c_int, [_P, C.c_uint64, C.POINTER(tpx_box)]),
+    "tpx_num_tiles": (C.c_uint64, [_P]),
+    "tpx_get_tile": (C.c_int, [_P, C.c_uint64, C.POINTER(tpx_tile)]),
+    "tpx_workspace_bytes": (C.c_uint64, [_P]),
+    "tpx_execute": (C.c_int, [_P, C.POINTER(_P), C.POINTER(_P), _P, _P]),
+    "tpx_prepare": (C.c_int, [_P, _P, _P]),
+    "tpx_workspace_forget": (None, [_P]),
+    "tpx_free": (None, [_P]),
+    "tpx_last_error": (C.c_char_p, []),
+    "tpx_set_option": (C.c_int, [C.c_char_p, C.c_uint64]),
+    "tpx_probe_copy": (C.c_int, [_P, _P, C.c_uint64, _P]),
+}
+for _name, (_res, _args) in _sigs.items():
+    _f = getattr(_lib, _name)
+    _f.restype = _res
+    _f.argtypes = _args
+EXPORTS = tuple(_sigs)
+
+
+def _check(st: int) -> None:
+    if st != TPX_OK:
+        raise TpxError(st, _lib.tpx_last_error().decode())
+
+
+def _model_struct(n_layers, hidden, n_heads, ffn, vocab_true, max_pos=1024, vocab_divisor=0,
+                  state_elem_bytes=(2, 4, 4, 4), tied_head=False) -> tpx_model:
+    m = tpx_model(n_layers, hidden, n_heads, ffn, vocab_true, max_pos, vocab_divisor, len(state_elem_bytes))
+    for i, b in enumerate(state_elem_bytes):
+        m.state_elem_bytes[i] = b
+    m.flags = MODEL_TIED_HEAD if tied_head else 0
+    return m
+
+
+def _parallel_struct(T, P, D, stage_first_layer=None, qkv_layout=0, w_transposed=0, rank_alive=None):
+    keep = []
+    p = tpx_parallel(T, P, D)
+    if stage_first_layer is not None:
+        arr = (C.c_uint32 * len(stage_first_layer))(*stage_first_layer)
+        keep.append(arr)
+        p.stage_first_layer = C.cast(arr, C.POINTER(C.c_uint32))
+    p.qkv_layout, p.w_transposed = qkv_layout, w_transposed
+    if rank_alive is not None:
+        arr = (C.c_uint8 * len(rank_alive))(*[1 if a else 0 for a in rank_alive])
+        keep.append(arr)
+        p.rank_alive = C.cast(arr, C.POINTER(C.c_uint8))
+    return p, keep
+
+
+class Plan:
+    """Owner of one tpx_plan_t handle."""
+
+    def __init__(self, handle: int, dst_cursors: Optional[list] = None):
+        self._h = _P(handle)
+        self.dst_cursors = dst_cursors
+
+    def close(self) -> None:
+        if self._h:
+            _lib.tpx_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()
+
+    def num_buffers(self, side: int) -> int:
+        return _lib.tpx_num_buffers(self._h, side)
+
+    def buffer_bytes(self, side: int, rank: int) -> int:
+        return _lib.tpx_buffer_bytes(self._h, side, rank)
+
+    def manifest(self, side: int, rank: int) -> list:
+        out = []
+        for i in range(_lib.tpx_num_entries(self._h, side, rank)):
+            e = tpx_entry()
+            _check(_lib.tpx_manifest(self._h, side, rank, i, C.byref(e)))
+            out.append(e)
+        return out
+
+    def stats(self) -> dict:
+        s = tpx_stats_t()
+        _check(_lib.tpx_stats(self._h, C.byref(s)))
+        return {n: getattr(s, n) for n, _ in tpx_stats_t._fields_}
+
+    def boxes(self) -> list:
+        out = []
+        for i in range(_lib.tpx_num_boxes(self._h)):
+            b = tpx_box()
+            _check(_lib.tpx_get_box(self._h, i, C.byref(b)))
+            out.append(b)
+        return out
+
+    def num_tiles(self) -> int:
+        return _lib.tpx_num_tiles(self._h)
+
+    def tiles(self) -> list:
+        out = []
+        for i in range(_lib.tpx_num_tiles(self._h)):
+            t = tpx_tile()
+            _check(_lib.tpx_get_tile(self._h, i, C.byref(t)))
+            out.append(t)
+        return out
+
+    def workspace_bytes(self) -> int:
+        return _lib.tpx_workspace_bytes(self._h)
+
+    def execute(self, src_ptrs: Sequence[int], dst_ptrs: Sequence[int], workspace_ptr: int, stream: int = 0) -> None:
+        """Launch the reshard. All pointers are device addresses (ints); stream is a hipStream_t (int)."""
+        src = (_P * max(1, len(src_ptrs)))(*[_P(p) for p in src_ptrs])
+        dst = (_P * max(1, len(dst_ptrs)))(*[_P(p) for p in dst_ptrs])
+        if len(src_ptrs) != self.num_buffers(SIDE_SRC) or len(dst_ptrs) != self.num_buffers(SIDE_DST):
+            raise TpxError(TPX_ERR_INVALID_ARG, "one pointer per rank buffer is required")
+        _check(_lib.tpx_execute(self._h, src, dst, _P(workspace_ptr), _P(stream)))
+
+    def prepare(self, workspace_ptr: int, stream: int = 0) -> None:
+        _check(_lib.tpx_prepare(self._h, _P(workspace_ptr), _P(stream)))
+
+    def workspace_forget(self) -> None:
+        _lib.tpx_workspace_forget(self._h)
+
+
+def tpx_plan(model: dict, src: dict, dst: dict) -> Plan:
+    """model: kwargs of the GPT-style model; src / dst: kwargs T, P, D[, stage_first_layer, qkv_layout,
+    w_transposed, rank_alive]."""
+    m = _model_struct(**model)
+    s, keep_s = _parallel_struct(**src)
+    d, keep_d = _parallel_struct(**dst)
+    h = _P()
+    _check(_lib.tpx_plan(C.byref(m), C.byref(s), C.byref(d), C.byref(h)))
+    del keep_s, keep_d
+    return Plan(h.value)
+
+
+def tpx_plan_dataset(n_samples: int, global_batch: int, D_src: int, D_dst: int, src_cursors: Sequence[int],
+                     index_elem_bytes: int = 8) -> Plan:
+    if len(src_cursors) != D_src:
+        raise TpxError(TPX_ERR_INVALID_ARG, "one cursor per source replica is required")
+    cur = (C.c_uint64 * max(1, D_src))(*src_cursors)
+    out = (C.c_uint64 * max(1, D_dst))()
+    h = _P()
+    _check(_lib.tpx_plan_dataset(n_samples, global_batch, index_elem_bytes, D_src, D_dst, cur, out, C.byref(h)))
+    return Plan(h.value, [int(out[i]) for i in range(D_dst)])
+
+
+def tpx_execute(plan: Plan, src_ptrs, dst_ptrs, workspace_ptr, stream=0) -> None:
+    plan.execute(src_ptrs, dst_ptrs, workspace_ptr, stream)
+
+
+def tpx_free(plan: Plan) -> None:
+    plan.close()
+
+
+def tpx_set_option(key: str, value: int) -> None:
+    _check(_lib.tpx_set_option(key.encode(), value))
+
+
+def tpx_probe_copy(dst_ptr: int, src_ptr: int, nbytes: int, stream: int = 0) -> None:
+    _check(_lib.tpx_probe_copy(_P(dst_ptr), _P(src_ptr), nbytes, _P(stream)))
+
+
+def tpx_param_name(name: int) -> Optional[str]:
+    s = _lib.tpx_param_name(name)
+    return s.decode() if s else None

@@ -1,0 +1,176 @@
+// C ABI of libtpx (declared in tpx.h): argument checking and hand-off to the planner and the HIP executor.
+#include <chrono>
+#include <cstring>
+#include <new>
+
+#include "tpx_internal.hpp"
+
+using namespace tpx;
+
+namespace {
+uint64_t now_ns() {
+  return uint64_t(std::chrono::duration_cast<std::chrono::nanoseconds>(
+                      std::chrono::steady_clock::now().time_since_epoch()).count());
+}
+
+tpx_status finish_plan(tpx_plan_s& p) {
+  coalesce_boxes(p.boxes);
+  if (tpx_status st = tile_boxes(p, tuning().tile_bytes)) return st;
+  if (tpx_status st = validate_tiles(p)) return st;
+  finish_stats(p);
+  return TPX_OK;
+}
+}  // namespace
+
+extern "C" {
+
+tpx_status tpx_plan(const tpx_model* model, const tpx_parallel* src, const tpx_parallel* dst, tpx_plan_t** out) {
+  if (!model || !src || !dst || !out) return fail(TPX_ERR_INVALID_ARG, "tpx_plan: NULL argument");
+  const uint64_t t0 = now_ns();
+  try {
+    if (tpx_status st = check_model(*model)) return st;
+    tpx_plan_s* p = new tpx_plan_s();
+    p->model = *model;
+    tpx_status st = build_side(*model, *src, p->side[0]);
+    if (!st) st = build_side(*model, *dst, p->side[1]);
+    if (!st) st = plan_model_moves(*p);
+    if (!st) st = finish_plan(*p);
+    if (st) { delete p; return st; }
+    p->stats.plan_ns = now_ns() - t0;
+    *out = p;
+    return TPX_OK;
+  } catch (const std::bad_alloc&) {
+    return fail(TPX_ERR_OOM, "tpx_plan: out of host memory");
+  }
+}
+
+tpx_status tpx_plan_dataset(uint64_t n_samples, uint32_t global_batch, uint32_t index_elem_bytes, uint32_t D_src,
+                            uint32_t D_dst, const uint64_t* src_cursors, uint64_t* dst_cursors, tpx_plan_t** out) {
+  if (!out || !dst_cursors) return fail(TPX_ERR_INVALID_ARG, "tpx_plan_dataset: NULL argument");
+  const uint64_t t0 = now_ns();
+  try {
+    tpx_plan_s* p = new tpx_plan_s();
+    p->is_dataset = true;
+    std::vector<uint64_t> cur;
+    tpx_status st = plan_dataset_moves(*p, n_samples, global_batch, index_elem_bytes, D_src, D_dst, src_cursors, cur);
+    if (!st) st = finish_plan(*p);
+    if (st) { delete p; return st; }
+    std::copy(cur.begin(), cur.end(), dst_cursors);
+    p->stats.plan_ns = now_ns() - t0;
+    *out = p;
+    return TPX_OK;
+  } catch (const std::bad_alloc&) {
+    return fail(TPX_ERR_OOM, "tpx_plan_dataset: out of host memory");
+  }
+}
+
+uint32_t tpx_num_buffers(const tpx_plan_t* p, int side) {
+  return (p && (side == 0 || side == 1)) ? uint32_t(p->side[side].bytes.size()) : 0;
+}
+
+uint64_t tpx_buffer_bytes(const tpx_plan_t* p, int side, uint32_t rank) {
+  if (!p || (side != 0 && side != 1) || rank >= p->side[side].bytes.size()) return 0;
+  return p->side[side].bytes[rank];
+}
+
+uint32_t tpx_num_entries(const tpx_plan_t* p, int side, uint32_t rank) {
+  if (!p || (side != 0 && side != 1) || rank >= p->side[side].ranks.size()) return 0;
+  return uint32_t(p->side[side].ranks[rank].size());
+}
+
+tpx_status tpx_manifest(const tpx_plan_t* p, int side, uint32_t rank, uint32_t i, tpx_entry* out) {
+  if (!p || !out || (side != 0 && side != 1) || rank >= p->side[side].ranks.size() ||
+      i >= p->side[side].ranks[rank].size())
+    return fail(TPX_ERR_INVALID_ARG, "tpx_manifest: bad argument");
+  *out = p->side[side].ranks[rank][i];
+  return TPX_OK;
+}
+
+const char* tpx_param_name(uint32_t name) { return param_name(name); }
+
+tpx_status tpx_stats(const tpx_plan_t* p, tpx_stats_t* out) {
+  if (!p || !out) return fail(TPX_ERR_INVALID_ARG, "tpx_stats: NULL argument");
+  *out = p->stats;
+  return TPX_OK;
+}
+
+uint64_t tpx_num_boxes(const tpx_plan_t* p) { return p ? p->boxes.size() : 0; }
+
+tpx_status tpx_get_box(const tpx_plan_t* p, uint64_t i, tpx_box* out) {
+  if (!p || !out || i >= p->boxes.size()) return fail(TPX_ERR_INVALID_ARG, "tpx_get_box: bad argument");
+  *out = p->boxes[i];
+  return TPX_OK;
+}
+
+uint64_t tpx_num_tiles(const tpx_plan_t* p) { return p ? p->tiles.size() : 0; }
+
+tpx_status tpx_get_tile(const tpx_plan_t* p, uint64_t i, tpx_tile* out) {
+  if (!p || !out || i >= p->tiles.size()) return fail(TPX_ERR_INVALID_ARG, "tpx_get_tile: bad argument");
+  *out = p->tiles[i];
+  return TPX_OK;
+}
+
+uint64_t tpx_workspace_bytes(const tpx_plan_t* p) {
+  return p ? std::max<uint64_t>(64, p->tiles.size() * sizeof(tpx_tile)) : 0;
+}
+
+tpx_status tpx_prepare(tpx_plan_t* p, void* workspace, void* hip_stream) {
+  if (!p || !workspace) return fail(TPX_ERR_INVALID_ARG, "tpx_prepare: NULL argument");
+  if (reinterpret_cast<uintptr_t>(workspace) % 64) return fail(TPX_ERR_INVALID_ARG, "tpx_prepare: workspace must be 64-byte aligned");
+  if (p->tiles.empty() || p->uploaded_ws == workspace) return TPX_OK;
+  if (tpx_status st = hip_upload_tiles(workspace, p->tiles.data(), p->tiles.size(), hip_stream)) return st;
+  p->uploaded_ws = workspace;
+  return TPX_OK;
+}
+
+tpx_status tpx_execute(tpx_plan_t* p, const void* const* src_bufs, void* const* dst_bufs, void* workspace,
+                       void* hip_stream) {
+  if (!p || !src_bufs || !dst_bufs || !workspace) return fail(TPX_ERR_INVALID_ARG, "tpx_execute: NULL argument");
+  const uint32_t ns = uint32_t(p->side[0].bytes.size()), nd = uint32_t(p->side[1].bytes.size());
+  for (uint32_t r = 0; r < ns; ++r) {
+    if (!src_bufs[r] && p->side[0].alive[r] && p->side[0].bytes[r])
+      return fail(TPX_ERR_INVALID_ARG, "tpx_execute: NULL source buffer for a live rank");
+    if (reinterpret_cast<uintptr_t>(src_bufs[r]) % 16) return fail(TPX_ERR_INVALID_ARG, "tpx_execute: source buffer not 16-byte aligned");
+  }
+  for (uint32_t r = 0; r < nd; ++r) {
+    if (!dst_bufs[r] && p->side[1].bytes[r]) return fail(TPX_ERR_INVALID_ARG, "tpx_execute: NULL destination buffer");
+    if (reinterpret_cast<uintptr_t>(dst_bufs[r]) % 16) return fail(TPX_ERR_INVALID_ARG, "tpx_execute: destination buffer not 16-byte aligned");
+  }
+  if (p->tiles.empty()) return TPX_OK;
+  if (tpx_status st = tpx_prepare(p, workspace, hip_stream)) return st;
+  return hip_launch_tiles(static_cast<const tpx_tile*>(workspace), p->tiles.size(), src_bufs, ns, dst_bufs, nd,
+                          tuning().variant, p->needs_lds, hip_stream);
+}
+
+void tpx_workspace_forget(tpx_plan_t* p) {
+  if (p) p->uploaded_ws = nullptr;
+}
+
+void tpx_free(tpx_plan_t* p) { delete p; }
+
+const char* tpx_last_error(void) { return last_error_cstr(); }
+
+tpx_status tpx_set_option(const char* key, uint64_t value) {
+  if (!key) return fail(TPX_ERR_INVALID_ARG, "tpx_set_option: NULL key");
+  if (!std::strcmp(key, "tile_bytes")) {
+    if (value < 4096 || value > 4194304 || (value & (value - 1)))
+      return fail(TPX_ERR_INVALID_ARG, "tile_bytes must be a power of two in [4096, 4194304]");
+    tuning().tile_bytes = value;
+    return TPX_OK;
+  }
+  if (!std::strcmp(key, "variant")) {
+    if (value > 15) return fail(TPX_ERR_INVALID_ARG, "variant out of range");
+    tuning().variant = value;
+    return TPX_OK;
+  }
+  return fail(TPX_ERR_INVALID_ARG, std::string("unknown option ") + key);
+}
+
+tpx_status tpx_probe_copy(void* dst, const void* src, uint64_t nbytes, void* hip_stream) {
+  if (!dst || !src) return fail(TPX_ERR_INVALID_ARG, "tpx_probe_copy: NULL argument");
+  if (nbytes % 16 || reinterpret_cast<uintptr_t>(dst) % 16 || reinterpret_cast<uintptr_t>(src) % 16)
+    return fail(TPX_ERR_INVALID_ARG, "tpx_probe_copy: size and pointers must be multiples of 16");
+  return hip_probe_copy(dst, src, nbytes, hip_stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,216 @@
+// The PTC of one configuration (paper section 4.1, equation 1), evaluated on the host:
+// sigma (how each tensor is sliced), phi (which stage and replica holds a slice) and
+// alpha (which rank buffer that is, and where inside it).  The paper leaves the concrete
+// functions to the model parallelizer; the Megatron-style rules here are this library's
+// own convention.
+#include <algorithm>
+#include <cstring>
+
+#include "tpx_internal.hpp"
+
+namespace tpx {
+
+namespace {
+thread_local std::string g_err;
+const char* kNames[N_NAMES] = {
+    "word_embeddings.weight", "position_embeddings.weight",
+    "input_layernorm.weight", "input_layernorm.bias",
+    "attention.query_key_value.weight", "attention.query_key_value.bias",
+    "attention.dense.weight", "attention.dense.bias",
+    "post_attention_layernorm.weight", "post_attention_layernorm.bias",
+    "mlp.dense_h_to_4h.weight", "mlp.dense_h_to_4h.bias",
+    "mlp.dense_4h_to_h.weight", "mlp.dense_4h_to_h.bias",
+    "final_layernorm.weight", "final_layernorm.bias"};
+}  // namespace
+
+tpx_status fail(tpx_status st, const std::string& msg) {
+  g_err = msg;
+  return st;
+}
+const char* last_error_cstr() { return g_err.c_str(); }
+
+Tuning& tuning() {
+  static Tuning t;
+  return t;
+}
+
+const char* param_name(uint32_t name) { return name < N_NAMES ? kNames[name] : nullptr; }
+
+uint32_t tensor_id_of(uint32_t name, int32_t layer) {
+  switch (name) {
+    case WORD_EMB: return 0;
+    case POS_EMB: return 1;
+    case LNF_W: return 2;
+    case LNF_B: return 3;
+    default: return 4 + uint32_t(layer) * kLayerNames + (name - LN1_W);
+  }
+}
+
+uint32_t n_tensors_of(const tpx_model& m) { return 4 + m.n_layers * kLayerNames; }
+
+tpx_status check_model(const tpx_model& m) {
+  if (!m.n_layers || !m.hidden || !m.n_heads || !m.ffn || !m.vocab_true || !m.max_pos)
+    return fail(TPX_ERR_INVALID_ARG, "model: a dimension is zero");
+  if (m.n_state_kinds < 1 || m.n_state_kinds > 4)
+    return fail(TPX_ERR_INVALID_ARG, "model: n_state_kinds must be 1..4");
+  for (uint32_t k = 0; k < m.n_state_kinds; ++k) {
+    uint8_t b = m.state_elem_bytes[k];
+    if (b != 1 && b != 2 && b != 4 && b != 8)
+      return fail(TPX_ERR_INVALID_ARG, "model: state element size must be 1, 2, 4 or 8 bytes");
+  }
+  if (m.hidden % m.n_heads) return fail(TPX_ERR_INDIVISIBLE, "model: hidden is not a multiple of n_heads");
+  return TPX_OK;
+}
+
+static tpx_status padded_vocab(const tpx_model& m, uint32_t T, uint64_t& out) {
+  if (m.vocab_divisor == 0) {
+    if (m.vocab_true % T) return fail(TPX_ERR_INDIVISIBLE, "vocabulary is not divisible by T and no padding divisor is set");
+    out = m.vocab_true;
+    return TPX_OK;
+  }
+  const uint64_t q = uint64_t(m.vocab_divisor) * T;
+  out = (m.vocab_true + q - 1) / q * q;
+  return TPX_OK;
+}
+
+// sigma: the slicing of one parameter tensor.
+tpx_status sigma_of(const tpx_model& m, const tpx_parallel& par, uint32_t name, Sigma& s) {
+  s = Sigma{};
+  const uint64_t h = m.hidden, a = m.n_heads, dh = m.hidden / m.n_heads, f = m.ffn;
+  const bool tr = par.w_transposed != 0;
+  auto set = [&](std::initializer_list<uint64_t> full, int axis, std::initializer_list<uint32_t> perm) {
+    s.ndim = uint32_t(full.size());
+    std::copy(full.begin(), full.end(), s.full);
+    std::copy(perm.begin(), perm.end(), s.perm);
+    s.split_axis = axis;
+  };
+  switch (name) {
+    case WORD_EMB: {  // vocabulary-parallel embedding: rows are cut
+      uint64_t vp = 0;
+      if (tpx_status st = padded_vocab(m, par.T, vp)) return st;
+      set({vp, h}, 0, {0, 1});
+      break;
+    }
+    case POS_EMB: set({m.max_pos, h}, -1, {0, 1}); break;
+    case LN1_W: case LN1_B: case LN2_W: case LN2_B: case DENSE_B: case FC2_B: case LNF_W: case LNF_B:
+      set({h}, -1, {0});
+      break;
+    case QKV_W:  // column-parallel, cut by heads; canonical view [head, q/k/v, head_dim, in]
+      if (par.qkv_layout == 0) {
+        if (tr) set({a, 3, dh, h}, 0, {3, 0, 1, 2}); else set({a, 3, dh, h}, 0, {0, 1, 2, 3});
+      } else {
+        if (tr) set({a, 3, dh, h}, 0, {3, 1, 0, 2}); else set({a, 3, dh, h}, 0, {1, 0, 2, 3});
+      }
+      break;
+    case QKV_B:
+      if (par.qkv_layout == 0) set({a, 3, dh}, 0, {0, 1, 2}); else set({a, 3, dh}, 0, {1, 0, 2});
+      break;
+    case DENSE_W:  // row-parallel: the input axis is cut
+      if (tr) set({h, h}, 1, {1, 0}); else set({h, h}, 1, {0, 1});
+      break;
+    case FC1_W:    // column-parallel
+      if (tr) set({f, h}, 0, {1, 0}); else set({f, h}, 0, {0, 1});
+      break;
+    case FC1_B: set({f}, 0, {0}); break;
+    case FC2_W:    // row-parallel
+      if (tr) set({h, f}, 1, {1, 0}); else set({h, f}, 1, {0, 1});
+      break;
+    default: return fail(TPX_ERR_INVALID_ARG, "unknown parameter name");
+  }
+  if (s.split_axis >= 0 && s.full[s.split_axis] % par.T)
+    return fail(TPX_ERR_INDIVISIBLE, std::string(kNames[name]) + ": sliced axis is not divisible by T");
+  return TPX_OK;
+}
+
+// phi + alpha: fill the manifests of all rank buffers of one configuration.
+tpx_status build_side(const tpx_model& m, const tpx_parallel& par, Side& out) {
+  if (!par.T || !par.P || !par.D) return fail(TPX_ERR_INVALID_ARG, "parallel degrees must be >= 1");
+  const uint64_t n_ranks = uint64_t(par.T) * par.P * par.D;
+  if (n_ranks > TPX_MAX_RANKS) return fail(TPX_ERR_INVALID_ARG, "more than TPX_MAX_RANKS ranks in one configuration");
+  if (par.qkv_layout > 1 || par.w_transposed > 1) return fail(TPX_ERR_INVALID_ARG, "unknown layout tag");
+  if (m.n_heads % par.T || m.ffn % par.T || m.hidden % par.T)
+    return fail(TPX_ERR_INDIVISIBLE, "heads, ffn or hidden not divisible by T");
+  out = Side{};
+  out.par = par;
+  out.stage_first.resize(par.P + 1);
+  if (par.stage_first_layer) {
+    for (uint32_t p = 0; p <= par.P; ++p) out.stage_first[p] = par.stage_first_layer[p];
+    if (out.stage_first[0] != 0 || out.stage_first[par.P] != m.n_layers)
+      return fail(TPX_ERR_BAD_STAGE_MAP, "stage boundaries must start at 0 and end at n_layers");
+    for (uint32_t p = 0; p < par.P; ++p)
+      if (out.stage_first[p] > out.stage_first[p + 1])
+        return fail(TPX_ERR_BAD_STAGE_MAP, "stage boundaries must be ascending");
+  } else {
+    if (m.n_layers % par.P) return fail(TPX_ERR_INDIVISIBLE, "layers not divisible by P and no stage map given");
+    for (uint32_t p = 0; p <= par.P; ++p) out.stage_first[p] = p * (m.n_layers / par.P);
+  }
+  out.par.stage_first_layer = nullptr;  // the copy above is authoritative; do not keep caller pointers
+  out.alive.assign(n_ranks, 1);
+  if (par.rank_alive) std::copy(par.rank_alive, par.rank_alive + n_ranks, out.alive.begin());
+  out.par.rank_alive = nullptr;
+
+  Sigma sig[N_NAMES];
+  for (uint32_t n = 0; n < N_NAMES; ++n)
+    if (tpx_status st = sigma_of(m, par, n, sig[n])) return st;
+
+  out.ranks.resize(n_ranks);
+  out.bytes.assign(n_ranks, 0);
+  out.holders.assign(size_t(n_tensors_of(m)) * m.n_state_kinds, {});
+
+  for (uint32_t p = 0; p < par.P; ++p) {
+    // the tensors of stage p in packing order
+    std::vector<std::pair<uint32_t, int32_t>> held;
+    if (p == 0) { held.push_back({WORD_EMB, -1}); held.push_back({POS_EMB, -1}); }
+    for (uint32_t l = out.stage_first[p]; l < out.stage_first[p + 1]; ++l)
+      for (uint32_t n = LN1_W; n <= FC2_B; ++n) held.push_back({n, int32_t(l)});
+    if (p == par.P - 1) {
+      held.push_back({LNF_W, -1});
+      held.push_back({LNF_B, -1});
+      if ((m.flags & TPX_MODEL_TIED_HEAD) && par.P > 1) held.push_back({WORD_EMB, -1});
+    }
+    for (uint32_t d = 0; d < par.D; ++d)
+      for (uint32_t t = 0; t < par.T; ++t) {
+        const uint32_t rank = t + par.T * (d + par.D * p);  // alpha
+        auto& man = out.ranks[rank];
+        man.reserve(held.size() * m.n_state_kinds);
+        uint64_t off = 0;
+        for (uint32_t k = 0; k < m.n_state_kinds; ++k)  // one arena per state kind
+          for (auto [name, layer] : held) {
+            const Sigma& s = sig[name];
+            tpx_entry e{};
+            e.tensor_id = tensor_id_of(name, layer);
+            e.kind = k;
+            e.elem_bytes = m.state_elem_bytes[k];
+            e.ndim = s.ndim;
+            e.name = name;
+            e.layer = layer;
+            uint64_t numel = 1;
+            for (uint32_t ax = 0; ax < s.ndim; ++ax) {
+              e.full_shape[ax] = s.full[ax];
+              e.lo[ax] = 0;
+              e.hi[ax] = s.full[ax];
+              e.perm[ax] = s.perm[ax];
+              if (int(ax) == s.split_axis) {
+                const uint64_t part = s.full[ax] / par.T;
+                e.lo[ax] = part * t;
+                e.hi[ax] = part * (t + 1);
+              }
+              numel *= e.hi[ax] - e.lo[ax];
+            }
+            off = (off + kAlign - 1) / kAlign * kAlign;
+            e.offset = off;
+            e.nbytes = numel * e.elem_bytes;
+            off += e.nbytes;
+            out.holders[size_t(e.tensor_id) * m.n_state_kinds + k].push_back({rank, uint32_t(man.size())});
+            man.push_back(e);
+          }
+        out.bytes[rank] = (off + kAlign - 1) / kAlign * kAlign;
+      }
+  }
+  // holders in ascending rank order, so "first alive holder" means lowest rank
+  for (auto& h : out.holders)
+    std::sort(h.begin(), h.end(), [](const Holder& x, const Holder& y) { return x.rank < y.rank; });
+  return TPX_OK;
+}
+
+}  // namespace tpx

@@ -1,0 +1,357 @@
+// Reconfiguration plan generation (paper section 4.2, algorithm 1), specialised to the case where
+// every resource is a buffer in one GPU's memory.
+//
+// The algorithm's three operations collapse into one record per piece:
+//   split(v, sigma, sigma')   - cut points of the old and the new slicing on the sliced axis give the
+//                               pieces w of a tensor that are contiguous in both an old and a new sub-tensor;
+//   move(w, r_w, r')          - r_w = get_resource(phi, alpha, w) is a surviving holder of w under the old
+//                               configuration, chosen for locality; r' is the new holder;
+//   merge(W)                  - the pieces of a new sub-tensor are adjacent again simply because each is
+//                               written at its own offset inside the new sub-tensor; nothing is staged.
+// The result is a list of boxes (tpx_box), then cut into equal-byte tiles for the GPU.
+#include <algorithm>
+#include <chrono>
+#include <cstring>
+
+#include "tpx_internal.hpp"
+
+namespace tpx {
+
+namespace {
+
+struct Axis {
+  uint64_t extent, ss, ds;  // strides in bytes
+};
+
+// Element strides (in elements) of each canonical axis inside a stored block.
+void stored_strides(const tpx_entry& e, uint64_t stride[4]) {
+  uint64_t acc = 1;
+  for (int i = int(e.ndim) - 1; i >= 0; --i) {
+    const uint32_t ax = e.perm[i];
+    stride[ax] = acc;
+    acc *= e.hi[ax] - e.lo[ax];
+  }
+}
+
+// Turn the piece [lo, hi) (canonical coordinates) of tensor blocks `se` (source, may be null for a
+// fill) and `de` (destination) into a box: drop unit axes, order by destination stride, fuse axes that
+// are nested the same way on both sides, and peel off the innermost run if it is contiguous on both.
+tpx_box lower_piece(const uint64_t lo[4], const uint64_t hi[4], const tpx_entry* se, uint32_t src_rank,
+                    const tpx_entry& de, uint32_t dst_rank) {
+  tpx_box b{};
+  const uint64_t eb = de.elem_bytes;
+  uint64_t sstr[4] = {0, 0, 0, 0}, dstr[4] = {0, 0, 0, 0};
+  stored_strides(de, dstr);
+  if (se) stored_strides(*se, sstr);
+  b.elem_bytes = uint32_t(eb);
+  b.tensor_id = de.tensor_id;
+  b.src_rank = se ? src_rank : 0;
+  b.dst_rank = dst_rank;
+  b.dst_off = de.offset;
+  b.src_off = se ? se->offset : 0;
+  std::vector<Axis> ax;
+  for (uint32_t k = 0; k < de.ndim; ++k) {
+    b.dst_off += (lo[k] - de.lo[k]) * dstr[k] * eb;
+    if (se) b.src_off += (lo[k] - se->lo[k]) * sstr[k] * eb;
+    if (hi[k] - lo[k] > 1) ax.push_back({hi[k] - lo[k], (se ? sstr[k] : dstr[k]) * eb, dstr[k] * eb});
+  }
+  std::sort(ax.begin(), ax.end(), [](const Axis& x, const Axis& y) { return x.ds != y.ds ? x.ds > y.ds : x.ss > y.ss; });
+  for (size_t i = 0; i + 1 < ax.size();) {
+    if (ax[i].ss == ax[i + 1].ss * ax[i + 1].extent && ax[i].ds == ax[i + 1].ds * ax[i + 1].extent) {
+      ax[i + 1].extent *= ax[i].extent;
+      ax.erase(ax.begin() + long(i));
+      if (i) --i;
+    } else {
+      ++i;
+    }
+  }
+  b.run_bytes = eb;
+  b.kind = se ? TPX_BOX_COPY : TPX_BOX_FILL;
+  if (!ax.empty() && ax.back().ds == eb && ax.back().ss == eb) {
+    b.run_bytes = ax.back().extent * eb;
+    ax.pop_back();
+  } else if (!ax.empty() && se) {
+    b.kind = TPX_BOX_TRANSPOSE;
+  }
+  b.ndim = uint32_t(ax.size());
+  for (size_t i = 0; i < ax.size(); ++i) {
+    b.extent[i] = ax[i].extent;
+    b.src_stride[i] = se ? ax[i].ss : 0;
+    b.dst_stride[i] = ax[i].ds;
+  }
+  return b;
+}
+
+uint64_t box_bytes(const tpx_box& b) {
+  uint64_t n = b.run_bytes;
+  for (uint32_t i = 0; i < b.ndim; ++i) n *= b.extent[i];
+  return n;
+}
+
+}  // namespace
+
+// get_resource(phi, alpha, w): among the surviving old holders of the old sub-tensor that contains
+// piece w, prefer (1) the one whose buffer index equals the destination's (the "same device": nothing
+// crosses), then (2) one with the destination's tensor-parallel index (only replicated tensors have a
+// choice here; it keeps a rank's neighbouring tensors coming from one source buffer, so their moves
+// merge), then (3) the lowest rank index.  Returns -1 if no holder survives.
+static int get_resource(const Side& src, const Side& dst, const std::vector<Holder>& hs, const uint64_t lo[4],
+                        const uint64_t hi[4], uint32_t ndim, uint32_t dst_rank) {
+  int best = -1, best_score = 3;
+  const uint32_t t_dst = dst_rank % dst.par.T;
+  for (size_t i = 0; i < hs.size(); ++i) {
+    const tpx_entry& e = src.ranks[hs[i].rank][hs[i].entry];
+    bool contains = true;
+    for (uint32_t k = 0; k < ndim; ++k) contains = contains && e.lo[k] <= lo[k] && hi[k] <= e.hi[k];
+    if (!contains || !src.alive[hs[i].rank]) continue;
+    const int score = hs[i].rank == dst_rank ? 0 : (hs[i].rank % src.par.T == t_dst ? 1 : 2);
+    if (score < best_score) { best = int(i); best_score = score; }
+  }
+  return best;
+}
+
+tpx_status plan_model_moves(tpx_plan_s& plan) {
+  const Side& S = plan.side[0];
+  const Side& Sn = plan.side[1];
+  const uint32_t nk = plan.model.n_state_kinds;
+  plan.boxes.clear();
+  uint64_t n_pieces = 0;
+  // RE-PARTITION: foreach r' in R', foreach sub-tensor s' allocated to r'
+  for (uint32_t rn = 0; rn < Sn.ranks.size(); ++rn) {
+    for (const tpx_entry& sn : Sn.ranks[rn]) {
+      const auto& hs = S.holders[size_t(sn.tensor_id) * nk + sn.kind];  // get_base_tensor: same tensor, old side
+      if (hs.empty()) return fail(TPX_ERR_INVALID_ARG, "tensor missing from the source configuration");
+      const tpx_entry& any = S.ranks[hs[0].rank][hs[0].entry];
+      // sliced axis: the one on which an old or new sub-tensor is narrower than the full tensor.
+      // Only the (padded) extent of axis 0 may differ between the two configurations.
+      int axis = -1;
+      for (uint32_t k = 0; k < sn.ndim; ++k) {
+        if (k > 0 && any.full_shape[k] != sn.full_shape[k]) return fail(TPX_ERR_INVALID_ARG, "tensor shapes differ between configurations");
+        if (sn.hi[k] - sn.lo[k] != sn.full_shape[k] || any.hi[k] - any.lo[k] != any.full_shape[k]) axis = int(k);
+      }
+      if (axis < 0 && any.full_shape[0] != sn.full_shape[0]) axis = 0;
+      uint64_t lo[4], hi[4];
+      for (uint32_t k = 0; k < 4; ++k) { lo[k] = sn.lo[k]; hi[k] = sn.hi[k]; }
+      if (axis < 0) {  // unsliced on both sides: a single piece
+        const int h = get_resource(S, Sn, hs, lo, hi, sn.ndim, rn);
+        if (h < 0) return fail(TPX_ERR_UNRECOVERABLE, std::string("no surviving holder of ") + param_name(sn.name) + " layer " + std::to_string(sn.layer));
+        plan.boxes.push_back(lower_piece(lo, hi, &S.ranks[hs[h].rank][hs[h].entry], hs[h].rank, sn, rn));
+        ++n_pieces;
+        continue;
+      }
+      // SPLIT: W = get_split_tensors(t, sigma, sigma'): walk the new sub-tensor's range on the sliced
+      // axis; the next cut point is the nearer of the old sub-tensor's end and the new one's end.
+      const uint64_t old_part = any.hi[axis] - any.lo[axis];  // equal parts under sigma
+      const uint64_t old_full = any.full_shape[axis];
+      uint64_t pos = sn.lo[axis];
+      const uint64_t end = sn.hi[axis];
+      while (pos < end && pos < old_full) {
+        const uint64_t old_end = (pos / old_part + 1) * old_part;
+        const uint64_t cut = std::min(std::min(old_end, end), old_full);
+        lo[axis] = pos;
+        hi[axis] = cut;
+        const int h = get_resource(S, Sn, hs, lo, hi, sn.ndim, rn);
+        if (h < 0) return fail(TPX_ERR_UNRECOVERABLE, std::string("no surviving holder of a piece of ") + param_name(sn.name) + " layer " + std::to_string(sn.layer));
+        plan.boxes.push_back(lower_piece(lo, hi, &S.ranks[hs[h].rank][hs[h].entry], hs[h].rank, sn, rn));  // move(w, r_w, r')
+        ++n_pieces;
+        pos = cut;
+      }
+      if (pos < end) {  // rows that exist only as new padding: zeros
+        lo[axis] = pos;
+        hi[axis] = end;
+        plan.boxes.push_back(lower_piece(lo, hi, nullptr, 0, sn, rn));
+      }
+      // merge(W): implicit - the pieces were addressed inside s' itself
+    }
+  }
+  plan.stats.n_pieces = n_pieces;
+  return TPX_OK;
+}
+
+// Two boxes that are plain runs, exact neighbours in both the source and the destination buffer
+// (no alignment gap in between), become one.
+void coalesce_boxes(std::vector<tpx_box>& boxes) {
+  std::vector<tpx_box> out;
+  out.reserve(boxes.size());
+  for (const tpx_box& b : boxes) {
+    if (!out.empty()) {
+      tpx_box& a = out.back();
+      const bool plain = a.ndim == 0 && b.ndim == 0 && a.kind == b.kind && a.kind != TPX_BOX_TRANSPOSE;
+      if (plain && a.dst_rank == b.dst_rank && a.dst_off + a.run_bytes == b.dst_off &&
+          (a.kind == TPX_BOX_FILL || (a.src_rank == b.src_rank && a.src_off + a.run_bytes == b.src_off))) {
+        a.run_bytes += b.run_bytes;
+        a.elem_bytes = std::min(a.elem_bytes, b.elem_bytes);
+        continue;
+      }
+    }
+    out.push_back(b);
+  }
+  boxes.swap(out);
+}
+
+namespace {
+
+uint32_t unit_log2_of(uint64_t bits) {  // largest power of two <= 16 dividing everything OR-ed into bits
+  uint32_t l = 0;
+  while (l < 4 && !(bits & (1ull << l))) ++l;
+  return l;
+}
+
+// Cut a span of `run` bytes into n near-equal chunks of at most tile_bytes, chunk sizes multiples of `quantum`.
+uint64_t chunk_of(uint64_t run, uint64_t tile_bytes, uint64_t quantum) {
+  if (run <= tile_bytes) return run;
+  const uint64_t n = (run + tile_bytes - 1) / tile_bytes;
+  uint64_t c = (run + n - 1) / n;
+  c = (c + quantum - 1) / quantum * quantum;
+  return std::min(c, tile_bytes);
+}
+
+}  // namespace
+
+tpx_status tile_boxes(tpx_plan_s& plan, uint64_t tile_bytes) {
+  plan.tiles.clear();
+  for (const tpx_box& b : plan.boxes) {
+    if (box_bytes(b) == 0) continue;
+    if (b.src_rank >= TPX_MAX_RANKS || b.dst_rank >= TPX_MAX_RANKS) return fail(TPX_ERR_INVALID_ARG, "rank out of range");
+    tpx_tile t{};
+    t.src_rank = uint16_t(b.src_rank);
+    t.dst_rank = uint16_t(b.dst_rank);
+    if (b.kind == TPX_BOX_TRANSPOSE) {
+      // Plane (I, J): J = axis contiguous on the source, I = axis contiguous on the destination; the other
+      // axes are enumerated.  When one axis is the finest on both sides (its contiguous partner had
+      // extent 1) the plane degenerates and elements are gathered one by one.
+      const uint64_t eb = b.elem_bytes;
+      uint32_t J = 0, I = 0;
+      for (uint32_t k = 1; k < b.ndim; ++k) {
+        if (b.src_stride[k] < b.src_stride[J]) J = k;
+        if (b.dst_stride[k] < b.dst_stride[I]) I = k;
+      }
+      uint32_t ulog = 0;
+      while ((1ull << ulog) < eb) ++ulog;
+      t.unit_log2 = uint8_t(ulog);
+      const bool plane = I != J && b.src_stride[J] == eb && b.dst_stride[I] == eb;
+      if (!plane) {  // rows along J only
+        I = J;
+        for (uint32_t k = 0; k < b.ndim; ++k) if (k != J) { I = k; break; }
+      }
+      t.kind = plane ? TPX_TILE_TRANSPOSE : TPX_TILE_GATHER;
+      const uint64_t nI = (I == J) ? 1 : b.extent[I], nJ = b.extent[J];
+      t.src_step = b.src_stride[J];
+      t.dst_step = b.dst_stride[J];
+      t.src_pitch = (I == J) ? 0 : b.src_stride[I];
+      t.dst_pitch = (I == J) ? 0 : b.dst_stride[I];
+      // chunk the plane: up to 256 rows (I) by as many columns (J) as fit the tile budget
+      const uint64_t rows_per = std::min<uint64_t>(nI, 256);
+      const uint64_t cols_per = std::max<uint64_t>(64, std::min<uint64_t>(nJ, tile_bytes / (rows_per * eb)));
+      uint64_t idx[4] = {0, 0, 0, 0};
+      for (;;) {  // odometer over the axes other than I and J
+        uint64_t so = b.src_off, d_o = b.dst_off;
+        for (uint32_t k = 0; k < b.ndim; ++k)
+          if (k != I && k != J) { so += idx[k] * b.src_stride[k]; d_o += idx[k] * b.dst_stride[k]; }
+        for (uint64_t i0 = 0; i0 < nI; i0 += rows_per)
+          for (uint64_t j0 = 0; j0 < nJ; j0 += cols_per) {
+            t.nrows = uint32_t(std::min(rows_per, nI - i0));
+            t.run_units = uint32_t(std::min(cols_per, nJ - j0));
+            t.src_off = so + i0 * t.src_pitch + j0 * t.src_step;
+            t.dst_off = d_o + i0 * t.dst_pitch + j0 * t.dst_step;
+            plan.tiles.push_back(t);
+          }
+        int k = int(b.ndim) - 1;
+        for (; k >= 0; --k) {
+          if (uint32_t(k) == I || uint32_t(k) == J) continue;
+          if (++idx[k] < b.extent[k]) break;
+          idx[k] = 0;
+        }
+        if (k < 0) break;
+      }
+      continue;
+    }
+    // COPY / FILL: the unit is the widest power of two (<= 16 bytes) that divides every offset,
+    // pitch and the run length; buffer bases are required to be 16-byte aligned.
+    uint64_t bits = b.dst_off | b.run_bytes | 16;
+    if (b.kind == TPX_BOX_COPY) bits |= b.src_off;
+    for (uint32_t k = 0; k < b.ndim; ++k) bits |= b.dst_stride[k] | (b.kind == TPX_BOX_COPY ? b.src_stride[k] : 0);
+    const uint32_t ulog = unit_log2_of(bits);
+    const uint64_t unit = 1ull << ulog;
+    t.kind = uint8_t(b.kind == TPX_BOX_COPY ? TPX_TILE_COPY : TPX_TILE_FILL);
+    t.unit_log2 = uint8_t(ulog);
+    t.src_step = t.dst_step = unit;
+    const uint64_t rows = b.ndim ? b.extent[b.ndim - 1] : 1;
+    const uint64_t sp = b.ndim ? b.src_stride[b.ndim - 1] : 0, dp = b.ndim ? b.dst_stride[b.ndim - 1] : 0;
+    const uint64_t quantum = std::max<uint64_t>(unit, (b.run_bytes % 256 == 0) ? 256 : unit);
+    const uint64_t chunk = chunk_of(b.run_bytes, tile_bytes, quantum);
+    const uint64_t rows_per = b.run_bytes >= tile_bytes ? 1 : std::max<uint64_t>(1, tile_bytes / b.run_bytes);
+    uint64_t idx[4] = {0, 0, 0, 0};
+    for (;;) {  // odometer over the outer axes except the last
+      uint64_t so = b.src_off, d_o = b.dst_off;
+      for (uint32_t k = 0; k + 1 < b.ndim; ++k) { so += idx[k] * b.src_stride[k]; d_o += idx[k] * b.dst_stride[k]; }
+      if (chunk < b.run_bytes) {  // long rows: each row is cut into contiguous tiles
+        for (uint64_t r = 0; r < rows; ++r)
+          for (uint64_t c0 = 0; c0 < b.run_bytes; c0 += chunk) {
+            t.nrows = 1;
+            t.run_units = uint32_t(std::min(chunk, b.run_bytes - c0) >> ulog);
+            t.src_pitch = t.dst_pitch = 0;
+            t.src_off = so + r * sp + c0;
+            t.dst_off = d_o + r * dp + c0;
+            plan.tiles.push_back(t);
+          }
+      } else {  // short rows: several whole rows per tile
+        for (uint64_t r = 0; r < rows; r += rows_per) {
+          t.nrows = uint32_t(std::min(rows_per, rows - r));
+          t.run_units = uint32_t(b.run_bytes >> ulog);
+          t.src_pitch = sp;
+          t.dst_pitch = dp;
+          t.src_off = so + r * sp;
+          t.dst_off = d_o + r * dp;
+          plan.tiles.push_back(t);
+        }
+      }
+      int k = int(b.ndim) - 2;
+      for (; k >= 0; --k) {
+        if (++idx[k] < b.extent[k]) break;
+        idx[k] = 0;
+      }
+      if (k < 0) break;
+    }
+  }
+  return TPX_OK;
+}
+
+// Host-side guard for the kernel: the first and last byte every tile touches lie inside the rank
+// buffers the manifests describe.
+tpx_status validate_tiles(tpx_plan_s& plan) {
+  plan.needs_lds = false;
+  for (const tpx_tile& t : plan.tiles) {
+    const uint64_t unit = 1ull << t.unit_log2;
+    if (!t.nrows || !t.run_units) return fail(TPX_ERR_INVALID_ARG, "internal: empty tile");
+    const uint64_t dlast = t.dst_off + (t.nrows - 1) * t.dst_pitch + (t.run_units - 1) * t.dst_step + unit;
+    if (t.dst_rank >= plan.side[1].bytes.size() || dlast > plan.side[1].bytes[t.dst_rank])
+      return fail(TPX_ERR_INVALID_ARG, "internal: tile writes outside its destination buffer");
+    if (t.kind != TPX_TILE_FILL) {
+      const uint64_t slast = t.src_off + (t.nrows - 1) * t.src_pitch + (t.run_units - 1) * t.src_step + unit;
+      if (t.src_rank >= plan.side[0].bytes.size() || slast > plan.side[0].bytes[t.src_rank])
+        return fail(TPX_ERR_INVALID_ARG, "internal: tile reads outside its source buffer");
+    }
+    if (t.kind == TPX_TILE_TRANSPOSE) plan.needs_lds = true;
+  }
+  return TPX_OK;
+}
+
+void finish_stats(tpx_plan_s& plan) {
+  tpx_stats_t& s = plan.stats;
+  s.n_boxes = plan.boxes.size();
+  s.n_tiles = plan.tiles.size();
+  s.bytes_read = s.bytes_written = s.bytes_fill = s.bytes_cross_rank = 0;
+  for (const tpx_box& b : plan.boxes) {
+    const uint64_t n = box_bytes(b);
+    s.bytes_written += n;
+    if (b.kind == TPX_BOX_FILL) {
+      s.bytes_fill += n;
+    } else {
+      s.bytes_read += n;
+      if (b.src_rank != b.dst_rank) s.bytes_cross_rank += n;
+    }
+  }
+}
+
+}  // namespace tpx

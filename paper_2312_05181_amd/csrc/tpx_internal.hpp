@@ -1,0 +1,92 @@
+// Internal declarations shared by the host planner, the C ABI and the HIP executor.
+#pragma once
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "tpx.h"
+
+namespace tpx {
+
+// The 16 parameter tensors of the GPT-style model, in the order a rank buffer packs them.
+enum Name : uint32_t {
+  WORD_EMB = 0, POS_EMB, LN1_W, LN1_B, QKV_W, QKV_B, DENSE_W, DENSE_B,
+  LN2_W, LN2_B, FC1_W, FC1_B, FC2_W, FC2_B, LNF_W, LNF_B, N_NAMES
+};
+constexpr uint32_t kLayerNames = 12;  // LN1_W .. FC2_B
+constexpr uint64_t kAlign = 256;      // every stored tensor starts on a 256-byte boundary
+
+// sigma of one parameter tensor under one configuration: the canonical view of the full tensor,
+// the canonical axis that tensor parallelism cuts (or -1: replicated) and the storage order.
+struct Sigma {
+  uint32_t ndim = 0;
+  uint64_t full[4] = {1, 1, 1, 1};
+  int split_axis = -1;
+  uint32_t perm[4] = {0, 1, 2, 3};
+};
+
+struct Holder {
+  uint32_t rank;
+  uint32_t entry;  // index into Side::ranks[rank]
+};
+
+// One configuration applied to the model: phi and alpha evaluated for every rank.
+struct Side {
+  tpx_parallel par{};
+  std::vector<uint32_t> stage_first;          // P+1 boundaries
+  std::vector<uint8_t> alive;                 // per rank
+  std::vector<std::vector<tpx_entry>> ranks;  // manifest of every rank buffer
+  std::vector<uint64_t> bytes;                // size of every rank buffer
+  std::vector<std::vector<Holder>> holders;   // [tensor_id * n_kinds + kind] -> who stores a piece of it
+};
+
+// Error reporting: sets the thread-local message and returns `st`.
+tpx_status fail(tpx_status st, const std::string& msg);
+const char* last_error_cstr();
+
+const char* param_name(uint32_t name);
+uint32_t tensor_id_of(uint32_t name, int32_t layer);
+uint32_t n_tensors_of(const tpx_model& m);
+tpx_status check_model(const tpx_model& m);
+tpx_status sigma_of(const tpx_model& m, const tpx_parallel& par, uint32_t name, Sigma& out);
+tpx_status build_side(const tpx_model& m, const tpx_parallel& par, Side& out);
+
+struct Tuning {
+  uint64_t tile_bytes = 262144;
+  uint64_t variant = 0;
+};
+Tuning& tuning();
+
+}  // namespace tpx
+
+struct tpx_plan_s {
+  bool is_dataset = false;
+  tpx_model model{};
+  tpx::Side side[2];
+  std::vector<tpx_box> boxes;
+  std::vector<tpx_tile> tiles;
+  tpx_stats_t stats{};
+  bool needs_lds = false;       // some tile is staged through LDS
+  void* uploaded_ws = nullptr;  // device workspace that currently holds `tiles`
+};
+
+namespace tpx {
+
+// Planner stages (host).
+tpx_status plan_model_moves(tpx_plan_s& plan);                 // split + re-partition + merge -> boxes
+void       coalesce_boxes(std::vector<tpx_box>& boxes);        // merge neighbours
+tpx_status tile_boxes(tpx_plan_s& plan, uint64_t tile_bytes);  // boxes -> tiles
+tpx_status validate_tiles(tpx_plan_s& plan);                    // every access inside its buffer
+void       finish_stats(tpx_plan_s& plan);
+tpx_status plan_dataset_moves(tpx_plan_s& plan, uint64_t n_samples, uint32_t B, uint32_t elem_bytes,
+                              uint32_t D_src, uint32_t D_dst, const uint64_t* src_cursors,
+                              std::vector<uint64_t>& dst_cursors);
+
+// HIP executor (kernels.hip).
+tpx_status hip_upload_tiles(void* workspace, const tpx_tile* tiles, uint64_t n, void* stream);
+tpx_status hip_launch_tiles(const tpx_tile* dev_tiles, uint64_t n_tiles, const void* const* src, uint32_t n_src,
+                            void* const* dst, uint32_t n_dst, uint64_t variant, bool needs_lds, void* stream);
+tpx_status hip_probe_copy(void* dst, const void* src, uint64_t nbytes, void* stream);
+
+}  // namespace tpx

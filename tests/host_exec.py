@@ -1,0 +1,41 @@
+"""Test-side interpreters of a plan's public description (boxes and tiles), in numpy.
+They let the CPU tests check the host planner against the oracle without a GPU.
+They are not a product path: the library itself only ever executes plans with its HIP kernels."""
+from __future__ import annotations
+
+import numpy as np
+
+import paper_2312_05181_amd.binding as B
+
+
+def run_boxes(plan, src_bufs, dst_bufs, cover=None):
+    """Apply every box to numpy uint8 buffers. cover (list of int arrays) counts writes per byte."""
+    for b in plan.boxes():
+        ext = [int(b.extent[k]) for k in range(b.ndim)]
+        run = int(b.run_bytes)
+        for idx in np.ndindex(*ext) if ext else [()]:
+            so = int(b.src_off) + sum(i * int(b.src_stride[k]) for k, i in enumerate(idx))
+            do = int(b.dst_off) + sum(i * int(b.dst_stride[k]) for k, i in enumerate(idx))
+            if b.kind == B.BOX_FILL:
+                dst_bufs[b.dst_rank][do:do + run] = 0
+            else:
+                dst_bufs[b.dst_rank][do:do + run] = src_bufs[b.src_rank][so:so + run]
+            if cover is not None:
+                cover[b.dst_rank][do:do + run] += 1
+
+
+def run_tiles(plan, src_bufs, dst_bufs, cover=None):
+    """Apply every tile, unit by unit, exactly as the tile table defines it."""
+    for t in plan.tiles():
+        unit = 1 << t.unit_log2
+        i = np.arange(t.nrows, dtype=np.int64)[:, None, None]
+        j = np.arange(t.run_units, dtype=np.int64)[None, :, None]
+        k = np.arange(unit, dtype=np.int64)[None, None, :]
+        di = (int(t.dst_off) + i * int(t.dst_pitch) + j * int(t.dst_step) + k).reshape(-1)
+        if t.kind == B.TILE_FILL:
+            dst_bufs[t.dst_rank][di] = 0
+        else:
+            si = (int(t.src_off) + i * int(t.src_pitch) + j * int(t.src_step) + k).reshape(-1)
+            dst_bufs[t.dst_rank][di] = src_bufs[t.src_rank][si]
+        if cover is not None:
+            np.add.at(cover[t.dst_rank], di, 1)

@@ -1,0 +1,213 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, bit for bit.
+
+Small cases: every destination byte is compared with the oracle's output (including the poison in
+alignment gaps).  Full-size workloads: every destination tensor is compared on the GPU with its
+closed-form contents (the value function evaluated at the oracle's layout), gaps are checked to be
+untouched, and a sample of tensors goes through the CPU oracle itself."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2312_05181_amd as tpx
+import synth
+from oracle import dataset as ods
+from oracle import reshard as oreshard
+from oracle import spec
+from oracle.spec import Model, Parallel
+from tests import gpu_util as G
+from tests import helpers as H
+from tests.test_planner import ODD, ODD_MIX, PAIRS, SMALL, SMALL_MIX, WIDE, mk, pk, plan_for
+
+pytestmark = pytest.mark.gpu
+
+
+def _check_small(model, mix, src, dst, seed=17, **plan_kw):
+    src_cpu = H.make_src_bufs(model, src, seed, mix)
+    want = oreshard.reshard(model, src, dst, H.np_bufs(src_cpu))
+    plan = plan_for(model, src, dst, **plan_kw)
+    src_gpu = [b.cuda() for b in src_cpu]
+    got, _ = G.execute(plan, src_gpu)
+    torch.cuda.synchronize()
+    for r, (g, w) in enumerate(zip(got, want)):
+        assert np.array_equal(g.cpu().numpy(), w), f"rank {r}"
+    for a, b in zip(src_gpu, src_cpu):          # sources are only read
+        assert torch.equal(a.cpu(), b)
+    return plan
+
+
+@pytest.mark.parametrize("model,mix,src,dst", PAIRS)
+def test_small_reshards_match_oracle(cuda, model, mix, src, dst):
+    """Odd sizes: exercises 2-, 4-, 8- and 16-byte units, fills, transposes and gathers."""
+    print("case", model.hidden, src, dst, flush=True)
+    _check_small(model, mix, src, dst)
+
+
+@pytest.mark.parametrize("tile_bytes", [4096, 65536])
+@pytest.mark.parametrize("src,dst", [(Parallel(2, 2, 1), Parallel(4, 1, 2)), (Parallel(8, 1, 1), Parallel(1, 2, 1)),
+                                     (Parallel(4, 1, 1), Parallel(8, 2, 1, qkv_layout=1)),
+                                     (Parallel(2, 1, 1, w_transposed=1), Parallel(4, 2, 1))])
+def test_several_tiles_and_ragged_tails(cuda, tile_bytes, src, dst):
+    """16-byte path with many tiles per box, 2-D tiles with a ragged last tile, tied embedding copy."""
+    print("case", tile_bytes, src, dst, flush=True)
+    tpx.tpx_set_option("tile_bytes", tile_bytes)
+    try:
+        plan = _check_small(WIDE, synth.MIX_GPT, src, dst)
+        assert plan.num_tiles() > 100
+    finally:
+        tpx.tpx_set_option("tile_bytes", 262144)
+
+
+@pytest.mark.parametrize("variant", range(16))
+def test_every_kernel_variant(cuda, variant):
+    print("variant", variant, flush=True)
+    tpx.tpx_set_option("variant", variant)
+    tpx.tpx_set_option("tile_bytes", 16384)
+    try:
+        _check_small(WIDE, synth.MIX_GPT, Parallel(4, 1, 1), Parallel(2, 2, 1))
+        _check_small(ODD, ODD_MIX, Parallel(3, 1, 1), Parallel(4, 1, 1))
+    finally:
+        tpx.tpx_set_option("variant", 0)
+        tpx.tpx_set_option("tile_bytes", 262144)
+
+
+def test_tiny_config_and_layout_change(cuda):
+    """Workload 1 (Tiny GPT, (2,1,1) -> (4,2,1)) and the same with a qkv-major destination."""
+    model, src, dst, mix, seed = H.CONFIGS[1]
+    _check_small(model, mix, src, dst, seed)
+    _check_small(model, mix, src, Parallel(4, 2, 1, qkv_layout=1), seed)
+    _check_small(model, mix, Parallel(2, 1, 1, qkv_layout=1), Parallel(4, 2, 1, w_transposed=1), seed)
+
+
+def test_plan_can_be_executed_repeatedly_and_round_trips(cuda):
+    model, mix = WIDE, synth.MIX_GPT
+    a, b = Parallel(2, 2, 1), Parallel(4, 1, 2)
+    src = [x.cuda() for x in H.make_src_bufs(model, a, 9, mix)]
+    fwd, back = plan_for(model, a, b), plan_for(model, b, a)
+    mid, ws = G.execute(fwd, src)
+    mid2, _ = G.execute(fwd, src, workspace=ws)               # same workspace, second launch
+    torch.cuda.synchronize()
+    assert all(torch.equal(x, y) for x, y in zip(mid, mid2))
+    out, _ = G.execute(back, mid)
+    torch.cuda.synchronize()
+    for r in range(a.n_ranks):                                # A -> B -> A is the identity on tensor bytes
+        for e in spec.rank_manifest(model, a, r)[0]:
+            d = H.desc_of(e)
+            assert torch.equal(out[r][d.offset:d.offset + d.nbytes], src[r][d.offset:d.offset + d.nbytes])
+
+
+def test_failure_recovery_reads_only_survivors(cuda):
+    model, mix = SMALL, SMALL_MIX
+    src, dst = Parallel(2, 2, 2), Parallel(2, 1, 1)
+    alive = [1] * src.n_ranks
+    for t in range(2):
+        alive[spec.rank_of(src, t, 0, 0)] = 0
+        alive[spec.rank_of(src, t, 1, 1)] = 0
+    src_cpu = H.make_src_bufs(model, src, 5, mix)
+    want = oreshard.reshard(model, src, dst, H.np_bufs(src_cpu))
+    plan = plan_for(model, src, dst, rank_alive=alive)
+    src_gpu = [b.cuda() if alive[r] else torch.empty(0, dtype=torch.uint8, device="cuda") for r, b in enumerate(src_cpu)]
+    got, _ = G.execute(plan, src_gpu)            # lost ranks are passed as NULL pointers
+    torch.cuda.synchronize()
+    assert all(np.array_equal(g.cpu().numpy(), w) for g, w in zip(got, want))
+
+
+def test_execute_argument_errors(cuda):
+    plan = plan_for(SMALL, Parallel(2, 1, 1), Parallel(1, 1, 1))
+    src = [G.alloc(plan.buffer_bytes(0, r), 0) for r in range(2)]
+    dst = [G.alloc(plan.buffer_bytes(1, 0), 0)]
+    ws = G.alloc(plan.workspace_bytes() + 64)
+    with pytest.raises(tpx.TpxError):
+        tpx.tpx_execute(plan, [src[0].data_ptr(), 0], [dst[0].data_ptr()], ws.data_ptr())
+    with pytest.raises(tpx.TpxError):
+        tpx.tpx_execute(plan, [src[0].data_ptr() + 4, src[1].data_ptr()], [dst[0].data_ptr()], ws.data_ptr())
+    with pytest.raises(tpx.TpxError):
+        tpx.tpx_execute(plan, [s.data_ptr() for s in src], [dst[0].data_ptr()], ws.data_ptr() + 8)
+    with pytest.raises(tpx.TpxError):
+        tpx.tpx_execute(plan, [s.data_ptr() for s in src], [dst[0].data_ptr()], 0)
+    torch.cuda.synchronize()
+
+
+def test_probe_copy(cuda):
+    for n in (16, 4096 + 48, 1 << 24):
+        a = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda")
+        b = torch.zeros(n + 16, dtype=torch.uint8, device="cuda")
+        tpx.tpx_probe_copy(b.data_ptr(), a.data_ptr(), n, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert torch.equal(a, b[:n]) and not b[n:].any()
+
+
+# ---------------------------------------------------------------------------------------------
+# the full-size workloads, in the launch configuration the benchmark times
+# ---------------------------------------------------------------------------------------------
+def _sample_ids(model):
+    L = model.n_layers
+    ids = [0, 1, 2, 3]
+    for layer in sorted({0, L // 2 - 1, L - 1}):
+        ids += [4 + layer * 12 + k for k in range(12)]
+    return ids
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+def test_full_size_workload(cuda, cfg):
+    model, src, dst, mix, seed = H.CONFIGS[cfg]
+    print("workload", cfg, "allocating", flush=True)
+    plan = plan_for(model, src, dst)
+    src_descs = H.manifest_descs(model, src)
+    src_gpu = []
+    for r, (descs, n) in enumerate(src_descs):
+        assert plan.buffer_bytes(0, r) == n
+        b = G.alloc(n, H.SRC_GAP)
+        synth.fill_buffer(b, descs, seed, mix)
+        src_gpu.append(b)
+    print("workload", cfg, "executing", plan.stats(), flush=True)
+    got, _ = G.execute(plan, src_gpu)
+    torch.cuda.synchronize()
+    print("workload", cfg, "checking closed form", flush=True)
+    assert H.closed_form_mismatches(got, model, src, dst, seed, mix) == 0
+    for b, (descs, n) in zip(got, H.manifest_descs(model, dst)):
+        assert H.gaps_untouched(b, descs, H.POISON)
+    # a sample of tensors through the CPU oracle itself
+    print("workload", cfg, "checking sampled tensors against the oracle", flush=True)
+    src_lay, dst_lay = oreshard.Layout(model, src), oreshard.Layout(model, dst)
+
+    def read(rank, off, n):
+        return src_gpu[rank][off:off + n].cpu().numpy()
+
+    for tid in _sample_ids(model):
+        for kind in range(len(model.state_elem_bytes)):
+            for rank, e, block in oreshard.reshard_tensor(model, src, dst, src_lay, dst_lay, tid, kind, read):
+                have = got[rank][e.offset:e.offset + block.nbytes].cpu().numpy()
+                assert np.array_equal(have, block.reshape(-1).view(np.uint8)), (tid, kind, rank)
+    del got, src_gpu
+    torch.cuda.empty_cache()
+
+
+# ---------------------------------------------------------------------------------------------
+# dataset state
+# ---------------------------------------------------------------------------------------------
+def _dataset_case(n, Bsz, D, D2, s, seed=6):
+    Gord = synth.epoch_order(n, seed) if n else np.zeros(0, dtype=np.uint64)
+    parts = ods.partition(Gord, Bsz, D)
+    cur = ods.cursors_after(n, Bsz, D, s)
+    want_parts, want_cur = ods.repartition(parts, cur, Bsz, D2)
+    plan = tpx.tpx_plan_dataset(n, Bsz, D, D2, cur)
+    assert plan.dst_cursors == want_cur
+    src = [torch.from_numpy(p.view(np.uint8).copy()).cuda() if p.size else torch.empty(0, dtype=torch.uint8, device="cuda")
+           for p in parts]
+    got, _ = G.execute(plan, src)
+    torch.cuda.synchronize()
+    for j in range(D2):
+        assert np.array_equal(got[j].cpu().numpy().view(np.uint64), want_parts[j]), j
+
+
+@pytest.mark.parametrize("n,Bsz,D,D2,s", [(100, 24, 6, 4, 2), (101, 24, 4, 6, 3), (7, 12, 6, 4, 1), (0, 12, 2, 3, 0),
+                                          (768 * 50 + 256, 768, 6, 4, 20), (100000, 768, 4, 6, 130), (1000, 48, 6, 6, 7)])
+def test_dataset_small(cuda, n, Bsz, D, D2, s):
+    print("dataset", n, Bsz, D, D2, s, flush=True)
+    _dataset_case(n, Bsz, D, D2, s)
+
+
+def test_dataset_full_size(cuda):
+    c = H.DATASET_CFG
+    print("dataset full size", c, flush=True)
+    _dataset_case(c["n_samples"], c["global_batch"], c["D_src"], c["D_dst"], c["steps_done"], c["seed"])

@@ -55,6 +55,8 @@ def main() -> int:
     ap.add_argument("--tile-bytes", type=int, default=0)
     ap.add_argument("--variant", type=int, default=-1)
     ap.add_argument("--no-probe", action="store_true")
+    ap.add_argument("--fill", choices=["synth", "cheap"], default="synth",
+                    help="source contents: seeded synthetic state, or one cheap fill per buffer (for profiler runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (all partitions of both configurations live in one "
@@ -91,7 +93,10 @@ def main() -> int:
     src_bufs, dst_bufs = [], []
     for r in range(n_src):
         b = torch.empty(plan.buffer_bytes(0, r), dtype=torch.uint8, device="cuda")
-        synth.fill_buffer(b, descs_of(0, r), seed, mix)
+        if args.fill == "synth":
+            synth.fill_buffer(b, descs_of(0, r), seed, mix)
+        else:
+            b.fill_(r + 1)
         src_bufs.append(b)
     for r in range(n_dst):
         dst_bufs.append(torch.zeros(plan.buffer_bytes(1, r), dtype=torch.uint8, device="cuda"))

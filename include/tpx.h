@@ -109,8 +109,9 @@ typedef struct {
   uint64_t dst_stride[4]; /* bytes */
 } tpx_box;
 
-/* One unit of GPU work: a bounded piece of one box, executed by one workgroup.  The device-side tile
- * table is an array of exactly this struct.  Unit (i, j), 0 <= i < nrows, 0 <= j < run_units, of
+/* One unit of GPU work: a bounded piece of one box, executed by one workgroup.  Tiles are not stored:
+ * the kernel (and tpx_get_tile, with the same code) derives tile number b from a compact box table.
+ * Unit (i, j), 0 <= i < nrows, 0 <= j < run_units, of
  * 1 << unit_log2 bytes goes from  src_off + i*src_pitch + j*src_step  to
  * dst_off + i*dst_pitch + j*dst_step. */
 #define TPX_TILE_COPY 0u      /* src_step == dst_step == unit: rows are contiguous on both sides */
@@ -128,7 +129,7 @@ typedef struct {
   uint8_t  kind;
   uint8_t  unit_log2;         /* 4 (16-byte vectors) when offsets, pitches and run length allow, else smaller */
   uint8_t  pad_[2];
-} tpx_tile;                   /* 64 bytes */
+} tpx_tile;
 
 typedef struct {
   uint64_t n_pieces;          /* sub-tensor pieces produced by the split step */
@@ -169,7 +170,7 @@ tpx_status tpx_get_box(const tpx_plan_t*, uint64_t i, tpx_box* out);
 uint64_t   tpx_num_tiles(const tpx_plan_t*);
 tpx_status tpx_get_tile(const tpx_plan_t*, uint64_t i, tpx_tile* out);
 
-/* DEVICE bytes tpx_execute needs in `workspace` (the tile table). */
+/* DEVICE bytes tpx_execute needs in `workspace` (the plan tables: flat boxes and tile prefix sums). */
 uint64_t   tpx_workspace_bytes(const tpx_plan_t*);
 
 /* Apply the plan (section 5.1, step 4): one kernel launch on `hip_stream` (a hipStream_t, NULL = the
@@ -178,7 +179,7 @@ uint64_t   tpx_workspace_bytes(const tpx_plan_t*);
  * ranks may be NULL.  workspace is a DEVICE pointer to tpx_workspace_bytes() bytes, 64-byte aligned.
  * Every destination tensor byte is written exactly once; bytes between tensors are left untouched;
  * sources are only read and must not overlap destinations.  The call does not wait for the kernel.
- * The first call with a given workspace copies the tile table into it and waits for that copy;
+ * The first call with a given workspace copies the plan tables into it and waits for that copy;
  * later calls with the same workspace reuse it, so the caller must not modify the workspace in
  * between (see tpx_workspace_forget()).  A plan may be executed any number of times; concurrent
  * executions of one plan must use the same, already filled workspace.
@@ -186,19 +187,21 @@ uint64_t   tpx_workspace_bytes(const tpx_plan_t*);
 tpx_status tpx_execute(tpx_plan_t*, const void* const* src_bufs, void* const* dst_bufs,
                        void* workspace, void* hip_stream);
 
-/* Optional: copy the tile table into `workspace` now (and wait for the copy), so that a following
+/* Optional: copy the plan tables into `workspace` now (and wait for the copy), so that a following
  * tpx_execute with the same workspace only launches the kernel.  Errors: INVALID_ARG, HIP. */
 tpx_status tpx_prepare(tpx_plan_t*, void* workspace, void* hip_stream);
 
-/* Forget which workspace holds the tile table (call after overwriting or freeing it). */
+/* Forget which workspace holds the plan tables (call after overwriting or freeing it). */
 void tpx_workspace_forget(tpx_plan_t*);
 
 void tpx_free(tpx_plan_t*);
 const char* tpx_last_error(void);
 
 /* Global tuning knobs, read by later tpx_plan / tpx_execute calls on any thread:
- *   "tile_bytes"  upper bound of bytes per tile (power of two, 4096 .. 4194304; default 262144)
- *   "variant"     kernel variant (0 = default; others are documented in the kernel source)
+ *   "tile_bytes"  upper bound of bytes per tile (power of two, 4096 .. 4194304; default 262144); small jobs
+ *                 use smaller tiles, down to 16384, so that the launch still has thousands of workgroups
+ *   "variant"     kernel variant, a bit field documented in the kernel source (default 12: 256 threads per
+ *                 workgroup, four 16-byte loads in flight per thread, nontemporal loads and stores)
  * Errors: INVALID_ARG for an unknown key or a value out of range. */
 tpx_status tpx_set_option(const char* key, uint64_t value);
 

@@ -102,23 +102,23 @@ tpx_status tpx_get_box(const tpx_plan_t* p, uint64_t i, tpx_box* out) {
   return TPX_OK;
 }
 
-uint64_t tpx_num_tiles(const tpx_plan_t* p) { return p ? p->tiles.size() : 0; }
+uint64_t tpx_num_tiles(const tpx_plan_t* p) { return p ? p->n_tiles : 0; }
 
 tpx_status tpx_get_tile(const tpx_plan_t* p, uint64_t i, tpx_tile* out) {
-  if (!p || !out || i >= p->tiles.size()) return fail(TPX_ERR_INVALID_ARG, "tpx_get_tile: bad argument");
-  *out = p->tiles[i];
+  if (!p || !out || i >= p->n_tiles) return fail(TPX_ERR_INVALID_ARG, "tpx_get_tile: bad argument");
+  // the same search and arithmetic the kernel performs
+  const uint32_t box = find_box(p->first_tile.data(), p->coarse.data(), uint32_t(p->flat.size()), uint32_t(i));
+  *out = tile_of(p->flat[box], uint32_t(i) - p->flat[box].first_tile);
   return TPX_OK;
 }
 
-uint64_t tpx_workspace_bytes(const tpx_plan_t* p) {
-  return p ? std::max<uint64_t>(64, p->tiles.size() * sizeof(tpx_tile)) : 0;
-}
+uint64_t tpx_workspace_bytes(const tpx_plan_t* p) { return p ? workspace_layout(*p).total : 0; }
 
 tpx_status tpx_prepare(tpx_plan_t* p, void* workspace, void* hip_stream) {
   if (!p || !workspace) return fail(TPX_ERR_INVALID_ARG, "tpx_prepare: NULL argument");
   if (reinterpret_cast<uintptr_t>(workspace) % 64) return fail(TPX_ERR_INVALID_ARG, "tpx_prepare: workspace must be 64-byte aligned");
-  if (p->tiles.empty() || p->uploaded_ws == workspace) return TPX_OK;
-  if (tpx_status st = hip_upload_tiles(workspace, p->tiles.data(), p->tiles.size(), hip_stream)) return st;
+  if (p->n_tiles == 0 || p->uploaded_ws == workspace) return TPX_OK;
+  if (tpx_status st = hip_upload_tables(workspace, *p, hip_stream)) return st;
   p->uploaded_ws = workspace;
   return TPX_OK;
 }
@@ -136,10 +136,9 @@ tpx_status tpx_execute(tpx_plan_t* p, const void* const* src_bufs, void* const* 
     if (!dst_bufs[r] && p->side[1].bytes[r]) return fail(TPX_ERR_INVALID_ARG, "tpx_execute: NULL destination buffer");
     if (reinterpret_cast<uintptr_t>(dst_bufs[r]) % 16) return fail(TPX_ERR_INVALID_ARG, "tpx_execute: destination buffer not 16-byte aligned");
   }
-  if (p->tiles.empty()) return TPX_OK;
+  if (p->n_tiles == 0) return TPX_OK;
   if (tpx_status st = tpx_prepare(p, workspace, hip_stream)) return st;
-  return hip_launch_tiles(static_cast<const tpx_tile*>(workspace), p->tiles.size(), src_bufs, ns, dst_bufs, nd,
-                          tuning().variant, p->needs_lds, hip_stream);
+  return hip_launch_tiles(workspace, *p, src_bufs, ns, dst_bufs, nd, tuning().variant, hip_stream);
 }
 
 void tpx_workspace_forget(tpx_plan_t* p) {
@@ -159,7 +158,7 @@ tpx_status tpx_set_option(const char* key, uint64_t value) {
     return TPX_OK;
   }
   if (!std::strcmp(key, "variant")) {
-    if (value > 15) return fail(TPX_ERR_INVALID_ARG, "variant out of range");
+    if (value > 47) return fail(TPX_ERR_INVALID_ARG, "variant out of range");
     tuning().variant = value;
     return TPX_OK;
   }

@@ -1,20 +1,21 @@
 // HIP executor for gfx950: applies a whole reconfiguration plan (paper section 5.1, step 4: the split,
 // re-partition and merge operations of section 4.2) with one kernel launch.
 //
-// The plan reaches the GPU as a table of 64-byte tiles; workgroup b executes tile b.  A tile is a bounded
-// piece (at most `tile_bytes`) of one move, so every workgroup has about the same amount of work no
-// matter how uneven the moves are.  Nothing is contracted, so there is no MFMA work: the kernel is a
+// The plan reaches the GPU as a small table of flat boxes with the prefix sums of their tile counts;
+// workgroup b finds the box that owns tile b by a short search and derives the tile from the box's
+// tiling parameters.  A tile is a bounded piece (at most `tile_bytes`) of one move, so every workgroup has
+// about the same amount of work no matter how uneven the moves are.  Nothing is contracted, so there is no MFMA work: the kernel is a
 // gather/scatter of 16-byte vectors and is bound by HBM bandwidth.  Each thread keeps several independent
 // 16-byte loads in flight before storing them.  LDS is used only by transposing tiles.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <string>
 
 #include "tpx_internal.hpp"
 
 namespace {
 
-constexpr int kThreads = 256;
 
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
@@ -43,7 +44,7 @@ __device__ __forceinline__ V zero_of() {
 
 // Copy (or zero-fill) nrows rows of run_units units of type V.  Consecutive threads take consecutive
 // units of the row-major unit index space, so accesses are coalesced along each row on both sides.
-template <typename V, int U, bool NTL, bool NTS, bool FILL>
+template <typename V, int kThreads, int U, bool NTL, bool NTS, bool FILL>
 __device__ __forceinline__ void move_rows(const uint8_t* __restrict__ s, uint8_t* __restrict__ d, uint32_t run_units,
                                           uint32_t nrows, uint64_t sp, uint64_t dp) {
   const uint32_t total = run_units * nrows;
@@ -83,22 +84,22 @@ __device__ __forceinline__ void move_rows(const uint8_t* __restrict__ s, uint8_t
   }
 }
 
-template <int U, bool NTL, bool NTS, bool FILL>
+template <int kThreads, int U, bool NTL, bool NTS, bool FILL>
 __device__ __forceinline__ void move_rows_any(uint32_t unit_log2, const uint8_t* s, uint8_t* d, uint32_t run_units,
                                               uint32_t nrows, uint64_t sp, uint64_t dp) {
   switch (unit_log2) {
-    case 4: move_rows<v4u, U, NTL, NTS, FILL>(s, d, run_units, nrows, sp, dp); break;
-    case 3: move_rows<uint64_t, 2, false, false, FILL>(s, d, run_units, nrows, sp, dp); break;
-    case 2: move_rows<uint32_t, 2, false, false, FILL>(s, d, run_units, nrows, sp, dp); break;
-    case 1: move_rows<uint16_t, 2, false, false, FILL>(s, d, run_units, nrows, sp, dp); break;
-    default: move_rows<uint8_t, 2, false, false, FILL>(s, d, run_units, nrows, sp, dp); break;
+    case 4: move_rows<v4u, kThreads, U, NTL, NTS, FILL>(s, d, run_units, nrows, sp, dp); break;
+    case 3: move_rows<uint64_t, kThreads, 2, false, false, FILL>(s, d, run_units, nrows, sp, dp); break;
+    case 2: move_rows<uint32_t, kThreads, 2, false, false, FILL>(s, d, run_units, nrows, sp, dp); break;
+    case 1: move_rows<uint16_t, kThreads, 2, false, false, FILL>(s, d, run_units, nrows, sp, dp); break;
+    default: move_rows<uint8_t, kThreads, 2, false, false, FILL>(s, d, run_units, nrows, sp, dp); break;
   }
 }
 
 // Transposing tile: element (i, j) is contiguous in j on the source and in i on the destination.
 // Sub-tiles of TI x TJ elements go through LDS so that both the global reads and the global writes
 // are coalesced.  lds holds TI x (TJ + 1) elements of type E.
-template <typename E, int TI, int TJ>
+template <typename E, int kThreads, int TI, int TJ>
 __device__ __forceinline__ void transpose_tile(const uint8_t* __restrict__ s, uint8_t* __restrict__ d, uint32_t nJ,
                                                uint32_t nI, uint64_t sp, uint64_t dstep, void* lds_raw) {
   E(*lds)[TJ + 1] = reinterpret_cast<E(*)[TJ + 1]>(lds_raw);
@@ -118,7 +119,7 @@ __device__ __forceinline__ void transpose_tile(const uint8_t* __restrict__ s, ui
     }
 }
 
-template <typename E>
+template <typename E, int kThreads>
 __device__ __forceinline__ void gather_tile(const uint8_t* __restrict__ s, uint8_t* __restrict__ d, const tpx_tile& t) {
   const uint32_t total = t.run_units * t.nrows;
   for (uint32_t e = threadIdx.x; e < total; e += kThreads) {
@@ -130,46 +131,53 @@ __device__ __forceinline__ void gather_tile(const uint8_t* __restrict__ s, uint8
 
 constexpr int kLdsBytes = 64 * 65 * 4;  // largest transposing sub-tile
 
-template <int U, bool NTL, bool NTS>
-__global__ __launch_bounds__(kThreads) void tpx_execute_tiles(const tpx_tile* __restrict__ tiles, PtrTable ptrs) {
+template <int kThreads, int U, bool NTL, bool NTS>
+__global__ __launch_bounds__(kThreads) void tpx_execute_tiles(const tpx::FlatBox* __restrict__ boxes,
+                                                              const uint32_t* __restrict__ first_tile,
+                                                              const uint32_t* __restrict__ coarse, uint32_t n_boxes,
+                                                              PtrTable ptrs) {
   extern __shared__ __align__(16) uint8_t lds_raw[];
-  const tpx_tile t = tiles[blockIdx.x];  // uniform per workgroup
+  // locate this workgroup's tile: uniform for the whole workgroup, so these are scalar loads
+  const uint32_t box = tpx::find_box(first_tile, coarse, n_boxes, blockIdx.x);
+  const tpx::FlatBox fb = boxes[box];
+  const tpx_tile t = tpx::tile_of(fb, blockIdx.x - fb.first_tile);
   uint8_t* d = ptrs.dst[t.dst_rank] + t.dst_off;
   if (t.kind == TPX_TILE_FILL) {
-    move_rows_any<U, NTL, NTS, true>(t.unit_log2, nullptr, d, t.run_units, t.nrows, 0, t.dst_pitch);
+    move_rows_any<kThreads, U, NTL, NTS, true>(t.unit_log2, nullptr, d, t.run_units, t.nrows, 0, t.dst_pitch);
     return;
   }
   const uint8_t* s = ptrs.src[t.src_rank] + t.src_off;
   if (t.kind == TPX_TILE_COPY) {
-    move_rows_any<U, NTL, NTS, false>(t.unit_log2, s, d, t.run_units, t.nrows, t.src_pitch, t.dst_pitch);
+    move_rows_any<kThreads, U, NTL, NTS, false>(t.unit_log2, s, d, t.run_units, t.nrows, t.src_pitch, t.dst_pitch);
   } else if (t.kind == TPX_TILE_TRANSPOSE) {
     switch (t.unit_log2) {
-      case 3: transpose_tile<uint64_t, 32, 64>(s, d, t.run_units, t.nrows, t.src_pitch, t.dst_step, lds_raw); break;
-      case 2: transpose_tile<uint32_t, 64, 64>(s, d, t.run_units, t.nrows, t.src_pitch, t.dst_step, lds_raw); break;
-      case 1: transpose_tile<uint16_t, 64, 64>(s, d, t.run_units, t.nrows, t.src_pitch, t.dst_step, lds_raw); break;
-      default: transpose_tile<uint8_t, 64, 64>(s, d, t.run_units, t.nrows, t.src_pitch, t.dst_step, lds_raw); break;
+      case 3: transpose_tile<uint64_t, kThreads, 32, 64>(s, d, t.run_units, t.nrows, t.src_pitch, t.dst_step, lds_raw); break;
+      case 2: transpose_tile<uint32_t, kThreads, 64, 64>(s, d, t.run_units, t.nrows, t.src_pitch, t.dst_step, lds_raw); break;
+      case 1: transpose_tile<uint16_t, kThreads, 64, 64>(s, d, t.run_units, t.nrows, t.src_pitch, t.dst_step, lds_raw); break;
+      default: transpose_tile<uint8_t, kThreads, 64, 64>(s, d, t.run_units, t.nrows, t.src_pitch, t.dst_step, lds_raw); break;
     }
   } else {
     switch (t.unit_log2) {
-      case 3: gather_tile<uint64_t>(s, d, t); break;
-      case 2: gather_tile<uint32_t>(s, d, t); break;
-      case 1: gather_tile<uint16_t>(s, d, t); break;
-      default: gather_tile<uint8_t>(s, d, t); break;
+      case 3: gather_tile<uint64_t, kThreads>(s, d, t); break;
+      case 2: gather_tile<uint32_t, kThreads>(s, d, t); break;
+      case 1: gather_tile<uint16_t, kThreads>(s, d, t); break;
+      default: gather_tile<uint8_t, kThreads>(s, d, t); break;
     }
   }
 }
 
 // Plain grid-stride copy: each thread moves 4 independent 16-byte vectors per iteration.
-__global__ __launch_bounds__(kThreads) void tpx_probe_copy_kernel(v4u* __restrict__ d, const v4u* __restrict__ s, uint64_t n) {
-  const uint64_t stride = uint64_t(gridDim.x) * kThreads * 4;
-  for (uint64_t base = uint64_t(blockIdx.x) * kThreads * 4 + threadIdx.x; base < n; base += stride) {
+constexpr int kProbeThreads = 256;
+__global__ __launch_bounds__(kProbeThreads) void tpx_probe_copy_kernel(v4u* __restrict__ d, const v4u* __restrict__ s, uint64_t n) {
+  const uint64_t stride = uint64_t(gridDim.x) * kProbeThreads * 4;
+  for (uint64_t base = uint64_t(blockIdx.x) * kProbeThreads * 4 + threadIdx.x; base < n; base += stride) {
     v4u r[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k)
-      if (base + uint64_t(k) * kThreads < n) r[k] = s[base + uint64_t(k) * kThreads];
+      if (base + uint64_t(k) * kProbeThreads < n) r[k] = s[base + uint64_t(k) * kProbeThreads];
 #pragma unroll
     for (int k = 0; k < 4; ++k)
-      if (base + uint64_t(k) * kThreads < n) d[base + uint64_t(k) * kThreads] = r[k];
+      if (base + uint64_t(k) * kProbeThreads < n) d[base + uint64_t(k) * kProbeThreads] = r[k];
   }
 }
 
@@ -177,23 +185,40 @@ tpx_status hip_fail(hipError_t e, const char* what) {
   return tpx::fail(TPX_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
 }
 
-using KernelFn = void (*)(const tpx_tile*, PtrTable);
+using KernelFn = void (*)(const tpx::FlatBox*, const uint32_t*, const uint32_t*, uint32_t, PtrTable);
 
-template <int U>
+template <int T, int U>
 KernelFn pick_nt(bool ntl, bool nts) {
-  if (ntl) return nts ? tpx_execute_tiles<U, true, true> : tpx_execute_tiles<U, true, false>;
-  return nts ? tpx_execute_tiles<U, false, true> : tpx_execute_tiles<U, false, false>;
+  if (ntl) return nts ? tpx_execute_tiles<T, U, true, true> : tpx_execute_tiles<T, U, true, false>;
+  return nts ? tpx_execute_tiles<T, U, false, true> : tpx_execute_tiles<T, U, false, false>;
+}
+
+template <int T>
+KernelFn pick_unroll(uint64_t variant) {
+  const bool ntl = (variant >> 2) & 1, nts = (variant >> 3) & 1;
+  switch (variant & 3) {
+    case 1: return pick_nt<T, 8>(ntl, nts);
+    case 2: return pick_nt<T, 2>(ntl, nts);
+    case 3: return pick_nt<T, 1>(ntl, nts);
+    default: return pick_nt<T, 4>(ntl, nts);
+  }
 }
 
 // variant bits: [1:0] loads in flight per thread (0: 4, 1: 8, 2: 2, 3: 1); bit 2: nontemporal loads;
-// bit 3: nontemporal stores.
+// bit 3: nontemporal stores; bits [5:4] threads per workgroup (0: 256, 1: 1024, 2: 512).
+int threads_of(uint64_t variant) {
+  switch ((variant >> 4) & 3) {
+    case 1: return 1024;
+    case 2: return 512;
+    default: return 256;
+  }
+}
+
 KernelFn pick_kernel(uint64_t variant) {
-  const bool ntl = (variant >> 2) & 1, nts = (variant >> 3) & 1;
-  switch (variant & 3) {
-    case 1: return pick_nt<8>(ntl, nts);
-    case 2: return pick_nt<2>(ntl, nts);
-    case 3: return pick_nt<1>(ntl, nts);
-    default: return pick_nt<4>(ntl, nts);
+  switch (threads_of(variant)) {
+    case 1024: return pick_unroll<1024>(variant);
+    case 512: return pick_unroll<512>(variant);
+    default: return pick_unroll<256>(variant);
   }
 }
 
@@ -201,28 +226,48 @@ KernelFn pick_kernel(uint64_t variant) {
 
 namespace tpx {
 
-tpx_status hip_upload_tiles(void* workspace, const tpx_tile* tiles, uint64_t n, void* stream) {
+WorkspaceLayout workspace_layout(const tpx_plan_s& plan) {
+  auto up = [](uint64_t x) { return (x + 255) / 256 * 256; };
+  WorkspaceLayout w;
+  w.boxes_off = 0;
+  w.first_off = up(plan.flat.size() * sizeof(FlatBox));
+  w.coarse_off = w.first_off + up(plan.first_tile.size() * sizeof(uint32_t));
+  w.total = std::max<uint64_t>(256, w.coarse_off + up(plan.coarse.size() * sizeof(uint32_t)));
+  return w;
+}
+
+tpx_status hip_upload_tables(void* workspace, const tpx_plan_s& plan, void* stream) {
   hipStream_t st = static_cast<hipStream_t>(stream);
-  hipError_t e = hipMemcpyAsync(workspace, tiles, n * sizeof(tpx_tile), hipMemcpyHostToDevice, st);
-  if (e != hipSuccess) return hip_fail(e, "copying the tile table to the workspace");
+  const WorkspaceLayout w = workspace_layout(plan);
+  uint8_t* base = static_cast<uint8_t*>(workspace);
+  hipError_t e = hipMemcpyAsync(base + w.boxes_off, plan.flat.data(), plan.flat.size() * sizeof(FlatBox), hipMemcpyHostToDevice, st);
+  if (e == hipSuccess)
+    e = hipMemcpyAsync(base + w.first_off, plan.first_tile.data(), plan.first_tile.size() * sizeof(uint32_t), hipMemcpyHostToDevice, st);
+  if (e == hipSuccess)
+    e = hipMemcpyAsync(base + w.coarse_off, plan.coarse.data(), plan.coarse.size() * sizeof(uint32_t), hipMemcpyHostToDevice, st);
+  if (e != hipSuccess) return hip_fail(e, "copying the plan tables to the workspace");
   e = hipStreamSynchronize(st);
-  if (e != hipSuccess) return hip_fail(e, "waiting for the tile table copy");
+  if (e != hipSuccess) return hip_fail(e, "waiting for the plan table copy");
   return TPX_OK;
 }
 
-tpx_status hip_launch_tiles(const tpx_tile* dev_tiles, uint64_t n_tiles, const void* const* src, uint32_t n_src,
-                            void* const* dst, uint32_t n_dst, uint64_t variant, bool needs_lds, void* stream) {
-  if (n_tiles == 0) return TPX_OK;
-  if (n_tiles > 0x7fffffffull) return fail(TPX_ERR_INVALID_ARG, "too many tiles for one launch");
+tpx_status hip_launch_tiles(const void* workspace, const tpx_plan_s& plan, const void* const* src, uint32_t n_src,
+                            void* const* dst, uint32_t n_dst, uint64_t variant, void* stream) {
+  if (plan.n_tiles == 0) return TPX_OK;
+  if (plan.n_tiles > 0x7fffffffull) return fail(TPX_ERR_INVALID_ARG, "too many tiles for one launch");
   if (n_src > TPX_MAX_RANKS || n_dst > TPX_MAX_RANKS) return fail(TPX_ERR_INVALID_ARG, "too many rank buffers");
   PtrTable pt;
   for (uint32_t r = 0; r < TPX_MAX_RANKS; ++r) {
     pt.src[r] = r < n_src ? static_cast<const uint8_t*>(src[r]) : nullptr;
     pt.dst[r] = r < n_dst ? static_cast<uint8_t*>(dst[r]) : nullptr;
   }
+  const WorkspaceLayout w = workspace_layout(plan);
+  const uint8_t* base = static_cast<const uint8_t*>(workspace);
   KernelFn k = pick_kernel(variant);
-  hipLaunchKernelGGL(k, dim3(uint32_t(n_tiles)), dim3(kThreads), needs_lds ? kLdsBytes : 0,
-                     static_cast<hipStream_t>(stream), dev_tiles, pt);
+  hipLaunchKernelGGL(k, dim3(uint32_t(plan.n_tiles)), dim3(threads_of(variant)), plan.needs_lds ? kLdsBytes : 0,
+                     static_cast<hipStream_t>(stream), reinterpret_cast<const FlatBox*>(base + w.boxes_off),
+                     reinterpret_cast<const uint32_t*>(base + w.first_off),
+                     reinterpret_cast<const uint32_t*>(base + w.coarse_off), uint32_t(plan.flat.size()), pt);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(e, "launching the tile kernel");
   return TPX_OK;
@@ -231,9 +276,9 @@ tpx_status hip_launch_tiles(const tpx_tile* dev_tiles, uint64_t n_tiles, const v
 tpx_status hip_probe_copy(void* dst, const void* src, uint64_t nbytes, void* stream) {
   if (nbytes == 0) return TPX_OK;
   const uint64_t n = nbytes / 16;
-  const uint64_t want = (n + kThreads * 4 - 1) / (kThreads * 4);
+  const uint64_t want = (n + kProbeThreads * 4 - 1) / (kProbeThreads * 4);
   const uint32_t grid = uint32_t(want < 256 * 16 ? want : 256 * 16);
-  hipLaunchKernelGGL(tpx_probe_copy_kernel, dim3(grid), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
+  hipLaunchKernelGGL(tpx_probe_copy_kernel, dim3(grid), dim3(kProbeThreads), 0, static_cast<hipStream_t>(stream),
                      static_cast<v4u*>(dst), static_cast<const v4u*>(src), n);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(e, "launching the probe copy kernel");

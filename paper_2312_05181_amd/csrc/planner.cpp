@@ -208,129 +208,128 @@ uint64_t chunk_of(uint64_t run, uint64_t tile_bytes, uint64_t quantum) {
 
 }  // namespace
 
+// Boxes -> flat boxes (at most two-dimensional, with their tiling parameters), tile prefix sums and the
+// coarse search table.  Tiles are bounded by tile_bytes; on small jobs the bound is lowered so that
+// the launch still has thousands of workgroups.
 tpx_status tile_boxes(tpx_plan_s& plan, uint64_t tile_bytes) {
-  plan.tiles.clear();
+  plan.flat.clear();
+  uint64_t total = 0;
+  for (const tpx_box& b : plan.boxes) total += box_bytes(b);
+  while (tile_bytes > 16384 && total / tile_bytes < 8192) tile_bytes >>= 1;
+  plan.tile_bytes_used = tile_bytes;
   for (const tpx_box& b : plan.boxes) {
     if (box_bytes(b) == 0) continue;
     if (b.src_rank >= TPX_MAX_RANKS || b.dst_rank >= TPX_MAX_RANKS) return fail(TPX_ERR_INVALID_ARG, "rank out of range");
-    tpx_tile t{};
-    t.src_rank = uint16_t(b.src_rank);
-    t.dst_rank = uint16_t(b.dst_rank);
+    FlatBox f{};
+    f.src_rank = uint16_t(b.src_rank);
+    f.dst_rank = uint16_t(b.dst_rank);
+    uint32_t I = 0, J = 0;     // the two axes a flat box keeps; all others are enumerated
+    uint64_t nI = 1, nJ = 1;
     if (b.kind == TPX_BOX_TRANSPOSE) {
-      // Plane (I, J): J = axis contiguous on the source, I = axis contiguous on the destination; the other
-      // axes are enumerated.  When one axis is the finest on both sides (its contiguous partner had
-      // extent 1) the plane degenerates and elements are gathered one by one.
+      // Plane (I, J): J = axis contiguous on the source, I = axis contiguous on the destination.  When one
+      // axis is the finest on both sides (its contiguous partner had extent 1) the plane degenerates and
+      // elements are gathered one by one.
       const uint64_t eb = b.elem_bytes;
-      uint32_t J = 0, I = 0;
       for (uint32_t k = 1; k < b.ndim; ++k) {
         if (b.src_stride[k] < b.src_stride[J]) J = k;
         if (b.dst_stride[k] < b.dst_stride[I]) I = k;
       }
       uint32_t ulog = 0;
       while ((1ull << ulog) < eb) ++ulog;
-      t.unit_log2 = uint8_t(ulog);
+      f.unit_log2 = uint8_t(ulog);
       const bool plane = I != J && b.src_stride[J] == eb && b.dst_stride[I] == eb;
-      if (!plane) {  // rows along J only
+      if (!plane) {
         I = J;
         for (uint32_t k = 0; k < b.ndim; ++k) if (k != J) { I = k; break; }
       }
-      t.kind = plane ? TPX_TILE_TRANSPOSE : TPX_TILE_GATHER;
-      const uint64_t nI = (I == J) ? 1 : b.extent[I], nJ = b.extent[J];
-      t.src_step = b.src_stride[J];
-      t.dst_step = b.dst_stride[J];
-      t.src_pitch = (I == J) ? 0 : b.src_stride[I];
-      t.dst_pitch = (I == J) ? 0 : b.dst_stride[I];
-      // chunk the plane: up to 256 rows (I) by as many columns (J) as fit the tile budget
-      const uint64_t rows_per = std::min<uint64_t>(nI, 256);
-      const uint64_t cols_per = std::max<uint64_t>(64, std::min<uint64_t>(nJ, tile_bytes / (rows_per * eb)));
-      uint64_t idx[4] = {0, 0, 0, 0};
-      for (;;) {  // odometer over the axes other than I and J
-        uint64_t so = b.src_off, d_o = b.dst_off;
-        for (uint32_t k = 0; k < b.ndim; ++k)
-          if (k != I && k != J) { so += idx[k] * b.src_stride[k]; d_o += idx[k] * b.dst_stride[k]; }
-        for (uint64_t i0 = 0; i0 < nI; i0 += rows_per)
-          for (uint64_t j0 = 0; j0 < nJ; j0 += cols_per) {
-            t.nrows = uint32_t(std::min(rows_per, nI - i0));
-            t.run_units = uint32_t(std::min(cols_per, nJ - j0));
-            t.src_off = so + i0 * t.src_pitch + j0 * t.src_step;
-            t.dst_off = d_o + i0 * t.dst_pitch + j0 * t.dst_step;
-            plan.tiles.push_back(t);
-          }
-        int k = int(b.ndim) - 1;
-        for (; k >= 0; --k) {
-          if (uint32_t(k) == I || uint32_t(k) == J) continue;
-          if (++idx[k] < b.extent[k]) break;
-          idx[k] = 0;
-        }
-        if (k < 0) break;
+      f.kind = plane ? TPX_TILE_TRANSPOSE : TPX_TILE_GATHER;
+      nI = (I == J) ? 1 : b.extent[I];
+      nJ = b.extent[J];
+      f.src_step = b.src_stride[J];
+      f.dst_step = b.dst_stride[J];
+      f.src_pitch = (I == J) ? 0 : b.src_stride[I];
+      f.dst_pitch = (I == J) ? 0 : b.dst_stride[I];
+      f.rows_per_tile = uint32_t(std::min<uint64_t>(nI, 256));
+      f.chunk_units = uint32_t(std::max<uint64_t>(64, std::min<uint64_t>(nJ, tile_bytes / (f.rows_per_tile * eb))));
+    } else {
+      // COPY / FILL: the unit is the widest power of two (<= 16 bytes) that divides every offset, pitch
+      // and the run length; buffer bases are required to be 16-byte aligned.
+      uint64_t bits = b.dst_off | b.run_bytes | 16;
+      if (b.kind == TPX_BOX_COPY) bits |= b.src_off;
+      for (uint32_t k = 0; k < b.ndim; ++k) bits |= b.dst_stride[k] | (b.kind == TPX_BOX_COPY ? b.src_stride[k] : 0);
+      const uint32_t ulog = unit_log2_of(bits);
+      const uint64_t unit = 1ull << ulog;
+      f.kind = uint8_t(b.kind == TPX_BOX_COPY ? TPX_TILE_COPY : TPX_TILE_FILL);
+      f.unit_log2 = uint8_t(ulog);
+      f.src_step = f.dst_step = unit;
+      I = J = b.ndim ? b.ndim - 1 : 0;  // rows = the innermost outer axis; the run itself is the "J" extent
+      nI = b.ndim ? b.extent[b.ndim - 1] : 1;
+      nJ = b.run_bytes >> ulog;
+      f.src_pitch = b.ndim ? b.src_stride[b.ndim - 1] : 0;
+      f.dst_pitch = b.ndim ? b.dst_stride[b.ndim - 1] : 0;
+      if (b.run_bytes > tile_bytes) {  // long rows: each row is cut into contiguous chunks
+        const uint64_t quantum = std::max<uint64_t>(unit, (b.run_bytes % 256 == 0) ? 256 : unit);
+        f.rows_per_tile = 1;
+        f.chunk_units = uint32_t(chunk_of(b.run_bytes, tile_bytes, quantum) >> ulog);
+      } else {                         // short rows: several whole rows per tile
+        f.rows_per_tile = uint32_t(std::max<uint64_t>(1, tile_bytes / b.run_bytes));
+        f.chunk_units = uint32_t(nJ);
       }
-      continue;
     }
-    // COPY / FILL: the unit is the widest power of two (<= 16 bytes) that divides every offset,
-    // pitch and the run length; buffer bases are required to be 16-byte aligned.
-    uint64_t bits = b.dst_off | b.run_bytes | 16;
-    if (b.kind == TPX_BOX_COPY) bits |= b.src_off;
-    for (uint32_t k = 0; k < b.ndim; ++k) bits |= b.dst_stride[k] | (b.kind == TPX_BOX_COPY ? b.src_stride[k] : 0);
-    const uint32_t ulog = unit_log2_of(bits);
-    const uint64_t unit = 1ull << ulog;
-    t.kind = uint8_t(b.kind == TPX_BOX_COPY ? TPX_TILE_COPY : TPX_TILE_FILL);
-    t.unit_log2 = uint8_t(ulog);
-    t.src_step = t.dst_step = unit;
-    const uint64_t rows = b.ndim ? b.extent[b.ndim - 1] : 1;
-    const uint64_t sp = b.ndim ? b.src_stride[b.ndim - 1] : 0, dp = b.ndim ? b.dst_stride[b.ndim - 1] : 0;
-    const uint64_t quantum = std::max<uint64_t>(unit, (b.run_bytes % 256 == 0) ? 256 : unit);
-    const uint64_t chunk = chunk_of(b.run_bytes, tile_bytes, quantum);
-    const uint64_t rows_per = b.run_bytes >= tile_bytes ? 1 : std::max<uint64_t>(1, tile_bytes / b.run_bytes);
+    if (nI > 0xffffffffull || nJ > 0xffffffffull) return fail(TPX_ERR_INVALID_ARG, "a move is too large for 32-bit tile indices");
+    f.nrows = uint32_t(nI);
+    f.run_units = uint32_t(nJ);
+    f.chunks_per_row = (f.run_units + f.chunk_units - 1) / f.chunk_units;
     uint64_t idx[4] = {0, 0, 0, 0};
-    for (;;) {  // odometer over the outer axes except the last
-      uint64_t so = b.src_off, d_o = b.dst_off;
-      for (uint32_t k = 0; k + 1 < b.ndim; ++k) { so += idx[k] * b.src_stride[k]; d_o += idx[k] * b.dst_stride[k]; }
-      if (chunk < b.run_bytes) {  // long rows: each row is cut into contiguous tiles
-        for (uint64_t r = 0; r < rows; ++r)
-          for (uint64_t c0 = 0; c0 < b.run_bytes; c0 += chunk) {
-            t.nrows = 1;
-            t.run_units = uint32_t(std::min(chunk, b.run_bytes - c0) >> ulog);
-            t.src_pitch = t.dst_pitch = 0;
-            t.src_off = so + r * sp + c0;
-            t.dst_off = d_o + r * dp + c0;
-            plan.tiles.push_back(t);
-          }
-      } else {  // short rows: several whole rows per tile
-        for (uint64_t r = 0; r < rows; r += rows_per) {
-          t.nrows = uint32_t(std::min(rows_per, rows - r));
-          t.run_units = uint32_t(b.run_bytes >> ulog);
-          t.src_pitch = sp;
-          t.dst_pitch = dp;
-          t.src_off = so + r * sp;
-          t.dst_off = d_o + r * dp;
-          plan.tiles.push_back(t);
-        }
-      }
-      int k = int(b.ndim) - 2;
+    for (;;) {  // odometer over the enumerated axes
+      f.src_off = b.src_off;
+      f.dst_off = b.dst_off;
+      for (uint32_t k = 0; k < b.ndim; ++k)
+        if (k != I && k != J) { f.src_off += idx[k] * b.src_stride[k]; f.dst_off += idx[k] * b.dst_stride[k]; }
+      plan.flat.push_back(f);
+      int k = int(b.ndim) - 1;
       for (; k >= 0; --k) {
+        if (uint32_t(k) == I || uint32_t(k) == J) continue;
         if (++idx[k] < b.extent[k]) break;
         idx[k] = 0;
       }
       if (k < 0) break;
     }
   }
+  // prefix sums and coarse table
+  uint64_t n_tiles = 0;
+  plan.first_tile.resize(plan.flat.size() + 1);
+  for (size_t i = 0; i < plan.flat.size(); ++i) {
+    plan.flat[i].first_tile = uint32_t(n_tiles);
+    plan.first_tile[i] = uint32_t(n_tiles);
+    n_tiles += tiles_of(plan.flat[i]);
+    if (n_tiles > 0x7fffffffull) return fail(TPX_ERR_INVALID_ARG, "too many tiles for one launch");
+  }
+  plan.first_tile[plan.flat.size()] = uint32_t(n_tiles);
+  plan.n_tiles = n_tiles;
+  plan.coarse.assign(size_t((n_tiles >> kCoarseShift) + 2), plan.flat.empty() ? 0 : uint32_t(plan.flat.size() - 1));
+  size_t box = 0;
+  for (uint64_t t = 0; t < n_tiles; t += (1ull << kCoarseShift)) {
+    while (box + 1 < plan.flat.size() && plan.first_tile[box + 1] <= t) ++box;
+    plan.coarse[size_t(t >> kCoarseShift)] = uint32_t(box);
+  }
   return TPX_OK;
 }
 
-// Host-side guard for the kernel: the first and last byte every tile touches lie inside the rank
+// Host-side guard for the kernel: the first and last byte every flat box touches lie inside the rank
 // buffers the manifests describe.
 tpx_status validate_tiles(tpx_plan_s& plan) {
   plan.needs_lds = false;
-  for (const tpx_tile& t : plan.tiles) {
+  for (const FlatBox& t : plan.flat) {
     const uint64_t unit = 1ull << t.unit_log2;
-    if (!t.nrows || !t.run_units) return fail(TPX_ERR_INVALID_ARG, "internal: empty tile");
+    if (!t.nrows || !t.run_units || !t.rows_per_tile || !t.chunk_units) return fail(TPX_ERR_INVALID_ARG, "internal: empty flat box");
     const uint64_t dlast = t.dst_off + (t.nrows - 1) * t.dst_pitch + (t.run_units - 1) * t.dst_step + unit;
     if (t.dst_rank >= plan.side[1].bytes.size() || dlast > plan.side[1].bytes[t.dst_rank])
-      return fail(TPX_ERR_INVALID_ARG, "internal: tile writes outside its destination buffer");
+      return fail(TPX_ERR_INVALID_ARG, "internal: a move writes outside its destination buffer");
     if (t.kind != TPX_TILE_FILL) {
       const uint64_t slast = t.src_off + (t.nrows - 1) * t.src_pitch + (t.run_units - 1) * t.src_step + unit;
       if (t.src_rank >= plan.side[0].bytes.size() || slast > plan.side[0].bytes[t.src_rank])
-        return fail(TPX_ERR_INVALID_ARG, "internal: tile reads outside its source buffer");
+        return fail(TPX_ERR_INVALID_ARG, "internal: a move reads outside its source buffer");
     }
     if (t.kind == TPX_TILE_TRANSPOSE) plan.needs_lds = true;
   }
@@ -340,7 +339,7 @@ tpx_status validate_tiles(tpx_plan_s& plan) {
 void finish_stats(tpx_plan_s& plan) {
   tpx_stats_t& s = plan.stats;
   s.n_boxes = plan.boxes.size();
-  s.n_tiles = plan.tiles.size();
+  s.n_tiles = plan.n_tiles;
   s.bytes_read = s.bytes_written = s.bytes_fill = s.bytes_cross_rank = 0;
   for (const tpx_box& b : plan.boxes) {
     const uint64_t n = box_bytes(b);

@@ -5,6 +5,7 @@
 #include <string>
 #include <vector>
 
+#include "tile_math.hpp"
 #include "tpx.h"
 
 namespace tpx {
@@ -54,7 +55,7 @@ tpx_status build_side(const tpx_model& m, const tpx_parallel& par, Side& out);
 
 struct Tuning {
   uint64_t tile_bytes = 262144;
-  uint64_t variant = 0;
+  uint64_t variant = 12;  // 256 threads, 4 loads in flight, nontemporal loads and stores
 };
 Tuning& tuning();
 
@@ -65,10 +66,14 @@ struct tpx_plan_s {
   tpx_model model{};
   tpx::Side side[2];
   std::vector<tpx_box> boxes;
-  std::vector<tpx_tile> tiles;
+  std::vector<tpx::FlatBox> flat;     // what the GPU executes
+  std::vector<uint32_t> first_tile;   // flat.size() + 1 prefix sums of tiles
+  std::vector<uint32_t> coarse;       // box index of every 64th tile (+ sentinel)
+  uint64_t n_tiles = 0;
+  uint64_t tile_bytes_used = 0;
   tpx_stats_t stats{};
   bool needs_lds = false;       // some tile is staged through LDS
-  void* uploaded_ws = nullptr;  // device workspace that currently holds `tiles`
+  void* uploaded_ws = nullptr;  // device workspace that currently holds the tables
 };
 
 namespace tpx {
@@ -84,9 +89,14 @@ tpx_status plan_dataset_moves(tpx_plan_s& plan, uint64_t n_samples, uint32_t B, 
                               std::vector<uint64_t>& dst_cursors);
 
 // HIP executor (kernels.hip).
-tpx_status hip_upload_tiles(void* workspace, const tpx_tile* tiles, uint64_t n, void* stream);
-tpx_status hip_launch_tiles(const tpx_tile* dev_tiles, uint64_t n_tiles, const void* const* src, uint32_t n_src,
-                            void* const* dst, uint32_t n_dst, uint64_t variant, bool needs_lds, void* stream);
+// Workspace layout: flat boxes, then first_tile, then coarse, each section starting on a 256-byte boundary.
+struct WorkspaceLayout {
+  uint64_t boxes_off = 0, first_off = 0, coarse_off = 0, total = 0;
+};
+WorkspaceLayout workspace_layout(const tpx_plan_s& plan);
+tpx_status hip_upload_tables(void* workspace, const tpx_plan_s& plan, void* stream);
+tpx_status hip_launch_tiles(const void* workspace, const tpx_plan_s& plan, const void* const* src, uint32_t n_src,
+                            void* const* dst, uint32_t n_dst, uint64_t variant, void* stream);
 tpx_status hip_probe_copy(void* dst, const void* src, uint64_t nbytes, void* stream);
 
 }  // namespace tpx

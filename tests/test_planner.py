@@ -279,7 +279,7 @@ def test_tiles_are_bounded_and_vector_aligned_on_the_headline_workload():
     model, src, dst, _, _ = H.CONFIGS[4]
     plan = plan_for(model, src, dst)
     s = plan.stats()
-    assert s["n_tiles"] == plan.num_tiles() and plan.workspace_bytes() == 64 * s["n_tiles"]
+    assert s["n_tiles"] == plan.num_tiles() and plan.workspace_bytes() < (1 << 20)     # tiles are derived, not stored
     total = 0
     for i in range(0, plan.num_tiles(), 997):
         t = B.tpx_tile()

@@ -8,6 +8,11 @@ import ctypes as C
 import os
 from typing import Optional, Sequence
 
+# Device memory and streams come from PyTorch, so the process must use exactly one HIP runtime: the one
+# PyTorch ships.  libtpx.so names the runtime by soname only; importing torch first makes the dynamic
+# linker resolve it to the copy torch has already loaded.
+import torch  # noqa: F401
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtpx.so")
 

@@ -26,21 +26,41 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 
 GPT_STATE = (2, 4, 4, 4)
+_TINY = dict(n_layers=2, hidden=256, n_heads=4, ffn=1024, vocab_true=1024, max_pos=1024, state_elem_bytes=(4, 4, 4))
+_G13 = dict(n_layers=24, hidden=2048, n_heads=16, ffn=8192, vocab_true=50304, state_elem_bytes=GPT_STATE)
+_G27 = dict(n_layers=32, hidden=2560, n_heads=32, ffn=10240, vocab_true=50304, state_elem_bytes=GPT_STATE)
+_G67 = dict(n_layers=32, hidden=4096, n_heads=32, ffn=16384, vocab_true=50304, state_elem_bytes=GPT_STATE)
+_ODD = dict(n_layers=24, hidden=3072, n_heads=24, ffn=12288, vocab_true=50257, vocab_divisor=128, state_elem_bytes=GPT_STATE)
+_BERT = dict(n_layers=24, hidden=1024, n_heads=16, ffn=4096, vocab_true=30522, vocab_divisor=128, max_pos=512,
+             state_elem_bytes=GPT_STATE)
+
+
+def _c(T, P, D, **kw):
+    return dict(T=T, P=P, D=D, **kw)
+
+
 WORKLOADS = {
-    # name: (model kwargs, src, dst, synth mix name, seed)
-    "tiny_2L_h256_(2,1,1)->(4,2,1)": (dict(n_layers=2, hidden=256, n_heads=4, ffn=1024, vocab_true=1024, max_pos=1024,
-                                           state_elem_bytes=(4, 4, 4)), dict(T=2, P=1, D=1), dict(T=4, P=2, D=1), "tiny", 1),
-    "gpt1.3b_(4,2,1)->(2,4,1)": (dict(n_layers=24, hidden=2048, n_heads=16, ffn=8192, vocab_true=50304,
-                                      state_elem_bytes=GPT_STATE), dict(T=4, P=2, D=1), dict(T=2, P=4, D=1), "gpt", 2),
-    "gpt2.7b_(4,4,2)->(2,4,1)": (dict(n_layers=32, hidden=2560, n_heads=32, ffn=10240, vocab_true=50304,
-                                      state_elem_bytes=GPT_STATE), dict(T=4, P=4, D=2),
-                                 dict(T=2, P=4, D=1, stage_first_layer=(0, 7, 16, 25, 32)), "gpt", 3),
-    "gpt6.7b_(8,1,1)->(1,8,1)": (dict(n_layers=32, hidden=4096, n_heads=32, ffn=16384, vocab_true=50304,
-                                      state_elem_bytes=GPT_STATE), dict(T=8, P=1, D=1), dict(T=1, P=8, D=1), "gpt", 4),
-    "gpt_h3072_T3->T4_padded_vocab": (dict(n_layers=24, hidden=3072, n_heads=24, ffn=12288, vocab_true=50257,
-                                           vocab_divisor=128, state_elem_bytes=GPT_STATE),
-                                      dict(T=3, P=1, D=1), dict(T=4, P=1, D=1), "gpt", 5),
+    # the five workloads of the benchmark spec: name -> (model kwargs, src, dst, synth mix name, seed)
+    "tiny_2L_h256_(2,1,1)->(4,2,1)": (_TINY, _c(2, 1, 1), _c(4, 2, 1), "tiny", 1),
+    "gpt1.3b_(4,2,1)->(2,4,1)": (_G13, _c(4, 2, 1), _c(2, 4, 1), "gpt", 2),
+    "gpt2.7b_(4,4,2)->(2,4,1)": (_G27, _c(4, 4, 2), _c(2, 4, 1, stage_first_layer=(0, 7, 16, 25, 32)), "gpt", 3),
+    "gpt6.7b_(8,1,1)->(1,8,1)": (_G67, _c(8, 1, 1), _c(1, 8, 1), "gpt", 4),
+    "gpt_h3072_T3->T4_padded_vocab": (_ODD, _c(3, 1, 1), _c(4, 1, 1), "gpt", 5),
 }
+# the paper's own reconfigurations (sections 6.2, 6.3, 6.6, 6.8) at the same shapes
+PAPER_PAIRS = {}
+for _n, _m in (("gpt1.3b", _G13), ("gpt2.7b", _G27), ("gpt6.7b", _G67)):
+    if _n != "gpt6.7b":        # 94 GB source + 188 GB destination does not fit one GPU
+        PAPER_PAIRS[f"{_n}_(4,2,1)->(4,2,2)_dp"] = (_m, _c(4, 2, 1), _c(4, 2, 2), "gpt", 11)
+    PAPER_PAIRS[f"{_n}_(4,2,1)->(4,4,1)_pp"] = (_m, _c(4, 2, 1), _c(4, 4, 1), "gpt", 12)
+    PAPER_PAIRS[f"{_n}_(4,2,1)->(8,2,1)_tp"] = (_m, _c(4, 2, 1), _c(8, 2, 1), "gpt", 13)
+    PAPER_PAIRS[f"{_n}_(4,2,1)->(4,2,1)_redeploy"] = (_m, _c(4, 2, 1), _c(4, 2, 1), "gpt", 14)
+PAPER_PAIRS["gpt1.3b_(2,4,2)->(2,4,1)_elastic"] = (_G13, _c(2, 4, 2), _c(2, 4, 1), "gpt", 15)
+PAPER_PAIRS["gpt1.3b_(2,4,1)->(2,2,1)_elastic"] = (_G13, _c(2, 4, 1), _c(2, 2, 1), "gpt", 16)
+for _a, _b in (((1, 1, 4), (1, 1, 8)), ((1, 4, 1), (1, 8, 1)), ((4, 1, 1), (8, 1, 1))):
+    PAPER_PAIRS[f"bert-large_{_a}->{_b}".replace(" ", "")] = (_BERT, _c(*_a), _c(*_b), "gpt", 17)
+    PAPER_PAIRS[f"bert-large_{_b}->{_a}".replace(" ", "")] = (_BERT, _c(*_b), _c(*_a), "gpt", 18)
+WORKLOADS.update(PAPER_PAIRS)
 DEFAULT_WORKLOAD = "gpt6.7b_(8,1,1)->(1,8,1)"
 
 # HBM bytes per launch of the copy kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE runs, or None.

@@ -99,6 +99,8 @@ typedef struct {
 typedef struct {
   uint32_t kind;
   uint32_t src_rank, dst_rank;
+  uint32_t n_dst;           /* multicast: the same bytes also go, at the same offsets, to buffers          */
+  uint32_t dst_rank_stride; /* dst_rank + k*dst_rank_stride, k < n_dst (data-parallel replicas); n_dst >= 1 */
   uint32_t ndim;          /* number of outer axes used, 0..4 */
   uint32_t elem_bytes;
   uint32_t tensor_id;     /* of the first tensor it covers (boxes of neighbouring tensors may be merged) */
@@ -128,14 +130,15 @@ typedef struct {
   uint16_t src_rank, dst_rank;
   uint8_t  kind;
   uint8_t  unit_log2;         /* 4 (16-byte vectors) when offsets, pitches and run length allow, else smaller */
-  uint8_t  pad_[2];
+  uint8_t  n_dst;             /* written to buffers dst_rank + k*dst_rank_stride, k < n_dst */
+  uint8_t  dst_rank_stride;
 } tpx_tile;
 
 typedef struct {
   uint64_t n_pieces;          /* sub-tensor pieces produced by the split step */
   uint64_t n_boxes;           /* moves after merging neighbours */
   uint64_t n_tiles;
-  uint64_t bytes_read;        /* source bytes read (= bytes_written - bytes_fill) */
+  uint64_t bytes_read;        /* source bytes read; a move replicated to several destinations reads once */
   uint64_t bytes_written;     /* destination bytes written (= all destination tensor bytes) */
   uint64_t bytes_fill;        /* zero-filled destination bytes (vocabulary padding growth) */
   uint64_t bytes_cross_rank;  /* bytes whose source buffer index differs from the destination's */

@@ -57,7 +57,8 @@ class tpx_entry(C.Structure):
 
 
 class tpx_box(C.Structure):
-    _fields_ = [("kind", C.c_uint32), ("src_rank", C.c_uint32), ("dst_rank", C.c_uint32), ("ndim", C.c_uint32),
+    _fields_ = [("kind", C.c_uint32), ("src_rank", C.c_uint32), ("dst_rank", C.c_uint32), ("n_dst", C.c_uint32),
+                ("dst_rank_stride", C.c_uint32), ("ndim", C.c_uint32),
                 ("elem_bytes", C.c_uint32), ("tensor_id", C.c_uint32), ("src_off", C.c_uint64),
                 ("dst_off", C.c_uint64), ("run_bytes", C.c_uint64), ("extent", C.c_uint64 * 4),
                 ("src_stride", C.c_uint64 * 4), ("dst_stride", C.c_uint64 * 4)]
@@ -67,7 +68,8 @@ class tpx_tile(C.Structure):
     _fields_ = [("src_off", C.c_uint64), ("dst_off", C.c_uint64), ("src_pitch", C.c_uint64),
                 ("dst_pitch", C.c_uint64), ("src_step", C.c_uint64), ("dst_step", C.c_uint64),
                 ("run_units", C.c_uint32), ("nrows", C.c_uint32), ("src_rank", C.c_uint16),
-                ("dst_rank", C.c_uint16), ("kind", C.c_uint8), ("unit_log2", C.c_uint8), ("pad_", C.c_uint8 * 2)]
+                ("dst_rank", C.c_uint16), ("kind", C.c_uint8), ("unit_log2", C.c_uint8), ("n_dst", C.c_uint8),
+                ("dst_rank_stride", C.c_uint8)]
 
 
 class tpx_stats_t(C.Structure):

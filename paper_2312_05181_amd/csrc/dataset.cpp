@@ -78,6 +78,7 @@ tpx_status plan_dataset_moves(tpx_plan_s& plan, uint64_t n, uint32_t B, uint32_t
         bx.kind = TPX_BOX_COPY;
         bx.src_rank = uint32_t(j);
         bx.dst_rank = jn;
+        bx.n_dst = 1;
         bx.elem_bytes = eb;
         bx.src_off = (pos - j * b) * eb;
         bx.dst_off = (pos - jn * bn) * eb;
@@ -97,6 +98,7 @@ tpx_status plan_dataset_moves(tpx_plan_s& plan, uint64_t n, uint32_t B, uint32_t
         bx.kind = TPX_BOX_COPY;
         bx.src_rank = uint32_t(j);
         bx.dst_rank = jn;
+        bx.n_dst = 1;
         bx.elem_bytes = eb;
         bx.src_off = (full * b + (pos - j * b)) * eb;
         bx.dst_off = (full * bn + (pos - jn * bn)) * eb;

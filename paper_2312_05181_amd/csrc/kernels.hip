@@ -42,24 +42,40 @@ __device__ __forceinline__ V zero_of() {
   return z;
 }
 
+// Destinations of a tile: buffer dst_rank + c * stride for c < n (data-parallel replicas), same offset in each.
+struct DstSet {
+  uint8_t* const* table;  // rank -> base pointer
+  uint64_t off;
+  uint32_t rank, stride, n;
+  __device__ __forceinline__ uint8_t* base(uint32_t c) const { return table[rank + c * stride] + off; }
+};
+
 // Copy (or zero-fill) nrows rows of run_units units of type V.  Consecutive threads take consecutive
 // units of the row-major unit index space, so accesses are coalesced along each row on both sides.
-template <typename V, int kThreads, int U, bool NTL, bool NTS, bool FILL>
-__device__ __forceinline__ void move_rows(const uint8_t* __restrict__ s, uint8_t* __restrict__ d, uint32_t run_units,
+// MC: the loaded units are stored to every destination of the set (read once, write many).
+template <typename V, int kThreads, int U, bool NTL, bool NTS, bool FILL, bool MC>
+__device__ __forceinline__ void move_rows(const uint8_t* __restrict__ s, const DstSet& ds, uint32_t run_units,
                                           uint32_t nrows, uint64_t sp, uint64_t dp) {
   const uint32_t total = run_units * nrows;
+  const uint32_t n_dst = MC ? ds.n : 1;
+  uint8_t* const d0 = ds.base(0);
   uint32_t i = threadIdx.x;
   if (nrows == 1) {
     const V* sv = reinterpret_cast<const V*>(s);
-    V* dv = reinterpret_cast<V*>(d);
     for (; i + (U - 1) * kThreads < total; i += U * kThreads) {
       V r[U];
 #pragma unroll
       for (int k = 0; k < U; ++k) r[k] = FILL ? zero_of<V>() : ld<V, NTL>(sv + i + k * kThreads);
+      for (uint32_t c = 0; c < n_dst; ++c) {
+        V* dv = reinterpret_cast<V*>(MC ? ds.base(c) : d0);
 #pragma unroll
-      for (int k = 0; k < U; ++k) st<V, NTS>(dv + i + k * kThreads, r[k]);
+        for (int k = 0; k < U; ++k) st<V, NTS>(dv + i + k * kThreads, r[k]);
+      }
     }
-    for (; i < total; i += kThreads) st<V, NTS>(dv + i, FILL ? zero_of<V>() : ld<V, NTL>(sv + i));
+    for (; i < total; i += kThreads) {
+      const V v = FILL ? zero_of<V>() : ld<V, NTL>(sv + i);
+      for (uint32_t c = 0; c < n_dst; ++c) st<V, NTS>(reinterpret_cast<V*>(MC ? ds.base(c) : d0) + i, v);
+    }
   } else {
     for (; i + (U - 1) * kThreads < total; i += U * kThreads) {
       V r[U];
@@ -72,27 +88,31 @@ __device__ __forceinline__ void move_rows(const uint8_t* __restrict__ s, uint8_t
         doff[k] = row * dp + uint64_t(col) * sizeof(V);
         r[k] = FILL ? zero_of<V>() : ld<V, NTL>(reinterpret_cast<const V*>(s + row * sp + uint64_t(col) * sizeof(V)));
       }
+      for (uint32_t c = 0; c < n_dst; ++c) {
+        uint8_t* d = MC ? ds.base(c) : d0;
 #pragma unroll
-      for (int k = 0; k < U; ++k) st<V, NTS>(reinterpret_cast<V*>(d + doff[k]), r[k]);
+        for (int k = 0; k < U; ++k) st<V, NTS>(reinterpret_cast<V*>(d + doff[k]), r[k]);
+      }
     }
     for (; i < total; i += kThreads) {
       const uint32_t row = i / run_units;
       const uint32_t col = i - row * run_units;
       const V v = FILL ? zero_of<V>() : ld<V, NTL>(reinterpret_cast<const V*>(s + row * sp + uint64_t(col) * sizeof(V)));
-      st<V, NTS>(reinterpret_cast<V*>(d + row * dp + uint64_t(col) * sizeof(V)), v);
+      for (uint32_t c = 0; c < n_dst; ++c)
+        st<V, NTS>(reinterpret_cast<V*>((MC ? ds.base(c) : d0) + row * dp + uint64_t(col) * sizeof(V)), v);
     }
   }
 }
 
-template <int kThreads, int U, bool NTL, bool NTS, bool FILL>
-__device__ __forceinline__ void move_rows_any(uint32_t unit_log2, const uint8_t* s, uint8_t* d, uint32_t run_units,
+template <int kThreads, int U, bool NTL, bool NTS, bool FILL, bool MC>
+__device__ __forceinline__ void move_rows_any(uint32_t unit_log2, const uint8_t* s, const DstSet& ds, uint32_t run_units,
                                               uint32_t nrows, uint64_t sp, uint64_t dp) {
   switch (unit_log2) {
-    case 4: move_rows<v4u, kThreads, U, NTL, NTS, FILL>(s, d, run_units, nrows, sp, dp); break;
-    case 3: move_rows<uint64_t, kThreads, 2, false, false, FILL>(s, d, run_units, nrows, sp, dp); break;
-    case 2: move_rows<uint32_t, kThreads, 2, false, false, FILL>(s, d, run_units, nrows, sp, dp); break;
-    case 1: move_rows<uint16_t, kThreads, 2, false, false, FILL>(s, d, run_units, nrows, sp, dp); break;
-    default: move_rows<uint8_t, kThreads, 2, false, false, FILL>(s, d, run_units, nrows, sp, dp); break;
+    case 4: move_rows<v4u, kThreads, U, NTL, NTS, FILL, MC>(s, ds, run_units, nrows, sp, dp); break;
+    case 3: move_rows<uint64_t, kThreads, 2, false, false, FILL, MC>(s, ds, run_units, nrows, sp, dp); break;
+    case 2: move_rows<uint32_t, kThreads, 2, false, false, FILL, MC>(s, ds, run_units, nrows, sp, dp); break;
+    case 1: move_rows<uint16_t, kThreads, 2, false, false, FILL, MC>(s, ds, run_units, nrows, sp, dp); break;
+    default: move_rows<uint8_t, kThreads, 2, false, false, FILL, MC>(s, ds, run_units, nrows, sp, dp); break;
   }
 }
 
@@ -141,27 +161,36 @@ __global__ __launch_bounds__(kThreads) void tpx_execute_tiles(const tpx::FlatBox
   const uint32_t box = tpx::find_box(first_tile, coarse, n_boxes, blockIdx.x);
   const tpx::FlatBox fb = boxes[box];
   const tpx_tile t = tpx::tile_of(fb, blockIdx.x - fb.first_tile);
-  uint8_t* d = ptrs.dst[t.dst_rank] + t.dst_off;
+  const DstSet ds{ptrs.dst, t.dst_off, t.dst_rank, t.dst_rank_stride, t.n_dst};
+  const bool mc = t.n_dst > 1;
   if (t.kind == TPX_TILE_FILL) {
-    move_rows_any<kThreads, U, NTL, NTS, true>(t.unit_log2, nullptr, d, t.run_units, t.nrows, 0, t.dst_pitch);
+    if (mc) move_rows_any<kThreads, U, NTL, NTS, true, true>(t.unit_log2, nullptr, ds, t.run_units, t.nrows, 0, t.dst_pitch);
+    else move_rows_any<kThreads, U, NTL, NTS, true, false>(t.unit_log2, nullptr, ds, t.run_units, t.nrows, 0, t.dst_pitch);
     return;
   }
   const uint8_t* s = ptrs.src[t.src_rank] + t.src_off;
   if (t.kind == TPX_TILE_COPY) {
-    move_rows_any<kThreads, U, NTL, NTS, false>(t.unit_log2, s, d, t.run_units, t.nrows, t.src_pitch, t.dst_pitch);
-  } else if (t.kind == TPX_TILE_TRANSPOSE) {
-    switch (t.unit_log2) {
-      case 3: transpose_tile<uint64_t, kThreads, 32, 64>(s, d, t.run_units, t.nrows, t.src_pitch, t.dst_step, lds_raw); break;
-      case 2: transpose_tile<uint32_t, kThreads, 64, 64>(s, d, t.run_units, t.nrows, t.src_pitch, t.dst_step, lds_raw); break;
-      case 1: transpose_tile<uint16_t, kThreads, 64, 64>(s, d, t.run_units, t.nrows, t.src_pitch, t.dst_step, lds_raw); break;
-      default: transpose_tile<uint8_t, kThreads, 64, 64>(s, d, t.run_units, t.nrows, t.src_pitch, t.dst_step, lds_raw); break;
-    }
-  } else {
-    switch (t.unit_log2) {
-      case 3: gather_tile<uint64_t, kThreads>(s, d, t); break;
-      case 2: gather_tile<uint32_t, kThreads>(s, d, t); break;
-      case 1: gather_tile<uint16_t, kThreads>(s, d, t); break;
-      default: gather_tile<uint8_t, kThreads>(s, d, t); break;
+    if (mc) move_rows_any<kThreads, U, NTL, NTS, false, true>(t.unit_log2, s, ds, t.run_units, t.nrows, t.src_pitch, t.dst_pitch);
+    else move_rows_any<kThreads, U, NTL, NTS, false, false>(t.unit_log2, s, ds, t.run_units, t.nrows, t.src_pitch, t.dst_pitch);
+    return;
+  }
+  // transposing and gathering tiles: one pass per destination (they are rare; the source is re-read)
+  for (uint32_t c = 0; c < t.n_dst; ++c) {
+    uint8_t* d = ds.base(c);
+    if (t.kind == TPX_TILE_TRANSPOSE) {
+      switch (t.unit_log2) {
+        case 3: transpose_tile<uint64_t, kThreads, 32, 64>(s, d, t.run_units, t.nrows, t.src_pitch, t.dst_step, lds_raw); break;
+        case 2: transpose_tile<uint32_t, kThreads, 64, 64>(s, d, t.run_units, t.nrows, t.src_pitch, t.dst_step, lds_raw); break;
+        case 1: transpose_tile<uint16_t, kThreads, 64, 64>(s, d, t.run_units, t.nrows, t.src_pitch, t.dst_step, lds_raw); break;
+        default: transpose_tile<uint8_t, kThreads, 64, 64>(s, d, t.run_units, t.nrows, t.src_pitch, t.dst_step, lds_raw); break;
+      }
+    } else {
+      switch (t.unit_log2) {
+        case 3: gather_tile<uint64_t, kThreads>(s, d, t); break;
+        case 2: gather_tile<uint32_t, kThreads>(s, d, t); break;
+        case 1: gather_tile<uint16_t, kThreads>(s, d, t); break;
+        default: gather_tile<uint8_t, kThreads>(s, d, t); break;
+      }
     }
   }
 }

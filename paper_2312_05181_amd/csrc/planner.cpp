@@ -47,6 +47,8 @@ tpx_box lower_piece(const uint64_t lo[4], const uint64_t hi[4], const tpx_entry*
   b.tensor_id = de.tensor_id;
   b.src_rank = se ? src_rank : 0;
   b.dst_rank = dst_rank;
+  b.n_dst = 1;
+  b.dst_rank_stride = 0;
   b.dst_off = de.offset;
   b.src_off = se ? se->offset : 0;
   std::vector<Axis> ax;
@@ -110,60 +112,104 @@ static int get_resource(const Side& src, const Side& dst, const std::vector<Hold
   return best;
 }
 
+namespace {
+
+// SPLIT: W = get_split_tensors(t, sigma, sigma') for the new sub-tensor sn.  Walks sn's range on the sliced
+// axis; the next cut point is the nearer of the old sub-tensor's end and the new one's end.  Calls
+// fn(lo, hi, is_fill) per piece; is_fill marks rows that exist only as new padding.
+template <typename Fn>
+tpx_status for_each_piece(const tpx_entry& sn, const tpx_entry& any, Fn&& fn) {
+  // sliced axis: the one on which an old or new sub-tensor is narrower than the full tensor.
+  // Only the (padded) extent of axis 0 may differ between the two configurations.
+  int axis = -1;
+  for (uint32_t k = 0; k < sn.ndim; ++k) {
+    if (k > 0 && any.full_shape[k] != sn.full_shape[k]) return fail(TPX_ERR_INVALID_ARG, "tensor shapes differ between configurations");
+    if (sn.hi[k] - sn.lo[k] != sn.full_shape[k] || any.hi[k] - any.lo[k] != any.full_shape[k]) axis = int(k);
+  }
+  if (axis < 0 && any.full_shape[0] != sn.full_shape[0]) axis = 0;
+  uint64_t lo[4], hi[4];
+  for (uint32_t k = 0; k < 4; ++k) { lo[k] = sn.lo[k]; hi[k] = sn.hi[k]; }
+  if (axis < 0) return fn(lo, hi, false);  // unsliced on both sides: a single piece
+  const uint64_t old_part = any.hi[axis] - any.lo[axis];  // equal parts under sigma
+  const uint64_t old_full = any.full_shape[axis];
+  uint64_t pos = sn.lo[axis];
+  const uint64_t end = sn.hi[axis];
+  while (pos < end && pos < old_full) {
+    const uint64_t old_end = (pos / old_part + 1) * old_part;
+    const uint64_t cut = std::min(std::min(old_end, end), old_full);
+    lo[axis] = pos;
+    hi[axis] = cut;
+    if (tpx_status st = fn(lo, hi, false)) return st;
+    pos = cut;
+  }
+  if (pos < end) {
+    lo[axis] = pos;
+    hi[axis] = end;
+    if (tpx_status st = fn(lo, hi, true)) return st;
+  }
+  return TPX_OK;
+}
+
+}  // namespace
+
 tpx_status plan_model_moves(tpx_plan_s& plan) {
   const Side& S = plan.side[0];
   const Side& Sn = plan.side[1];
   const uint32_t nk = plan.model.n_state_kinds;
+  const uint32_t Tn = Sn.par.T, Dn = Sn.par.D, Pn = Sn.par.P;
   plan.boxes.clear();
   uint64_t n_pieces = 0;
-  // RE-PARTITION: foreach r' in R', foreach sub-tensor s' allocated to r'
-  for (uint32_t rn = 0; rn < Sn.ranks.size(); ++rn) {
-    for (const tpx_entry& sn : Sn.ranks[rn]) {
-      const auto& hs = S.holders[size_t(sn.tensor_id) * nk + sn.kind];  // get_base_tensor: same tensor, old side
-      if (hs.empty()) return fail(TPX_ERR_INVALID_ARG, "tensor missing from the source configuration");
-      const tpx_entry& any = S.ranks[hs[0].rank][hs[0].entry];
-      // sliced axis: the one on which an old or new sub-tensor is narrower than the full tensor.
-      // Only the (padded) extent of axis 0 may differ between the two configurations.
-      int axis = -1;
-      for (uint32_t k = 0; k < sn.ndim; ++k) {
-        if (k > 0 && any.full_shape[k] != sn.full_shape[k]) return fail(TPX_ERR_INVALID_ARG, "tensor shapes differ between configurations");
-        if (sn.hi[k] - sn.lo[k] != sn.full_shape[k] || any.hi[k] - any.lo[k] != any.full_shape[k]) axis = int(k);
+  // RE-PARTITION: foreach r' in R', foreach sub-tensor s' allocated to r'.  The D' replicas of one (t', p')
+  // hold identical sub-collections at identical offsets; replicas that also make the same source choices
+  // are served by one multicast move (read once, written to each), so they are planned together.
+  for (uint32_t pn = 0; pn < Pn; ++pn)
+    for (uint32_t tn = 0; tn < Tn; ++tn) {
+      const uint32_t r0 = tn + Tn * Dn * pn;  // replica d' = 0; replica d' is r0 + d' * T'
+      // pass 1: every replica's source choice for every piece (get_resource)
+      std::vector<std::vector<int>> choice(Dn);
+      for (uint32_t dn = 0; dn < Dn; ++dn) {
+        const uint32_t rn = r0 + dn * Tn;
+        for (const tpx_entry& sn : Sn.ranks[r0]) {
+          const auto& hs = S.holders[size_t(sn.tensor_id) * nk + sn.kind];  // get_base_tensor: same tensor, old side
+          if (hs.empty()) return fail(TPX_ERR_INVALID_ARG, "tensor missing from the source configuration");
+          const tpx_entry& any = S.ranks[hs[0].rank][hs[0].entry];
+          tpx_status st = for_each_piece(sn, any, [&](const uint64_t* lo, const uint64_t* hi, bool is_fill) -> tpx_status {
+            if (is_fill) { choice[dn].push_back(-1); return TPX_OK; }
+            const int h = get_resource(S, Sn, hs, lo, hi, sn.ndim, rn);
+            if (h < 0)
+              return fail(TPX_ERR_UNRECOVERABLE, std::string("no surviving holder of a piece of ") + param_name(sn.name) +
+                                                     " layer " + std::to_string(sn.layer));
+            choice[dn].push_back(h);
+            ++n_pieces;
+            return TPX_OK;
+          });
+          if (st) return st;
+        }
       }
-      if (axis < 0 && any.full_shape[0] != sn.full_shape[0]) axis = 0;
-      uint64_t lo[4], hi[4];
-      for (uint32_t k = 0; k < 4; ++k) { lo[k] = sn.lo[k]; hi[k] = sn.hi[k]; }
-      if (axis < 0) {  // unsliced on both sides: a single piece
-        const int h = get_resource(S, Sn, hs, lo, hi, sn.ndim, rn);
-        if (h < 0) return fail(TPX_ERR_UNRECOVERABLE, std::string("no surviving holder of ") + param_name(sn.name) + " layer " + std::to_string(sn.layer));
-        plan.boxes.push_back(lower_piece(lo, hi, &S.ranks[hs[h].rank][hs[h].entry], hs[h].rank, sn, rn));
-        ++n_pieces;
-        continue;
+      // pass 2: one set of moves per run of consecutive replicas with identical choices
+      for (uint32_t d0 = 0; d0 < Dn;) {
+        uint32_t d1 = d0 + 1;
+        while (d1 < Dn && choice[d1] == choice[d0]) ++d1;
+        const uint32_t rn = r0 + d0 * Tn;
+        size_t cursor = 0;
+        for (const tpx_entry& sn : Sn.ranks[rn]) {
+          const auto& hs = S.holders[size_t(sn.tensor_id) * nk + sn.kind];
+          const tpx_entry& any = S.ranks[hs[0].rank][hs[0].entry];
+          tpx_status st = for_each_piece(sn, any, [&](const uint64_t* lo, const uint64_t* hi, bool is_fill) -> tpx_status {
+            const int h = choice[d0][cursor++];
+            tpx_box b = is_fill ? lower_piece(lo, hi, nullptr, 0, sn, rn)
+                                : lower_piece(lo, hi, &S.ranks[hs[h].rank][hs[h].entry], hs[h].rank, sn, rn);  // move(w, r_w, r')
+            b.n_dst = d1 - d0;
+            b.dst_rank_stride = Tn;
+            plan.boxes.push_back(b);
+            return TPX_OK;
+          });
+          if (st) return st;
+          // merge(W): implicit - the pieces were addressed inside s' itself
+        }
+        d0 = d1;
       }
-      // SPLIT: W = get_split_tensors(t, sigma, sigma'): walk the new sub-tensor's range on the sliced
-      // axis; the next cut point is the nearer of the old sub-tensor's end and the new one's end.
-      const uint64_t old_part = any.hi[axis] - any.lo[axis];  // equal parts under sigma
-      const uint64_t old_full = any.full_shape[axis];
-      uint64_t pos = sn.lo[axis];
-      const uint64_t end = sn.hi[axis];
-      while (pos < end && pos < old_full) {
-        const uint64_t old_end = (pos / old_part + 1) * old_part;
-        const uint64_t cut = std::min(std::min(old_end, end), old_full);
-        lo[axis] = pos;
-        hi[axis] = cut;
-        const int h = get_resource(S, Sn, hs, lo, hi, sn.ndim, rn);
-        if (h < 0) return fail(TPX_ERR_UNRECOVERABLE, std::string("no surviving holder of a piece of ") + param_name(sn.name) + " layer " + std::to_string(sn.layer));
-        plan.boxes.push_back(lower_piece(lo, hi, &S.ranks[hs[h].rank][hs[h].entry], hs[h].rank, sn, rn));  // move(w, r_w, r')
-        ++n_pieces;
-        pos = cut;
-      }
-      if (pos < end) {  // rows that exist only as new padding: zeros
-        lo[axis] = pos;
-        hi[axis] = end;
-        plan.boxes.push_back(lower_piece(lo, hi, nullptr, 0, sn, rn));
-      }
-      // merge(W): implicit - the pieces were addressed inside s' itself
     }
-  }
   plan.stats.n_pieces = n_pieces;
   return TPX_OK;
 }
@@ -177,7 +223,8 @@ void coalesce_boxes(std::vector<tpx_box>& boxes) {
     if (!out.empty()) {
       tpx_box& a = out.back();
       const bool plain = a.ndim == 0 && b.ndim == 0 && a.kind == b.kind && a.kind != TPX_BOX_TRANSPOSE;
-      if (plain && a.dst_rank == b.dst_rank && a.dst_off + a.run_bytes == b.dst_off &&
+      if (plain && a.dst_rank == b.dst_rank && a.n_dst == b.n_dst && a.dst_rank_stride == b.dst_rank_stride &&
+          a.dst_off + a.run_bytes == b.dst_off &&
           (a.kind == TPX_BOX_FILL || (a.src_rank == b.src_rank && a.src_off + a.run_bytes == b.src_off))) {
         a.run_bytes += b.run_bytes;
         a.elem_bytes = std::min(a.elem_bytes, b.elem_bytes);
@@ -223,6 +270,9 @@ tpx_status tile_boxes(tpx_plan_s& plan, uint64_t tile_bytes) {
     FlatBox f{};
     f.src_rank = uint16_t(b.src_rank);
     f.dst_rank = uint16_t(b.dst_rank);
+    f.n_dst = uint8_t(b.n_dst);
+    f.dst_rank_stride = uint8_t(b.dst_rank_stride);
+    if (b.dst_rank + uint64_t(b.n_dst - 1) * b.dst_rank_stride >= TPX_MAX_RANKS) return fail(TPX_ERR_INVALID_ARG, "rank out of range");
     uint32_t I = 0, J = 0;     // the two axes a flat box keeps; all others are enumerated
     uint64_t nI = 1, nJ = 1;
     if (b.kind == TPX_BOX_TRANSPOSE) {
@@ -324,8 +374,12 @@ tpx_status validate_tiles(tpx_plan_s& plan) {
     const uint64_t unit = 1ull << t.unit_log2;
     if (!t.nrows || !t.run_units || !t.rows_per_tile || !t.chunk_units) return fail(TPX_ERR_INVALID_ARG, "internal: empty flat box");
     const uint64_t dlast = t.dst_off + (t.nrows - 1) * t.dst_pitch + (t.run_units - 1) * t.dst_step + unit;
-    if (t.dst_rank >= plan.side[1].bytes.size() || dlast > plan.side[1].bytes[t.dst_rank])
-      return fail(TPX_ERR_INVALID_ARG, "internal: a move writes outside its destination buffer");
+    if (!t.n_dst) return fail(TPX_ERR_INVALID_ARG, "internal: a move without destination");
+    for (uint32_t k = 0; k < t.n_dst; ++k) {
+      const uint32_t r = t.dst_rank + k * t.dst_rank_stride;
+      if (r >= plan.side[1].bytes.size() || dlast > plan.side[1].bytes[r])
+        return fail(TPX_ERR_INVALID_ARG, "internal: a move writes outside its destination buffer");
+    }
     if (t.kind != TPX_TILE_FILL) {
       const uint64_t slast = t.src_off + (t.nrows - 1) * t.src_pitch + (t.run_units - 1) * t.src_step + unit;
       if (t.src_rank >= plan.side[0].bytes.size() || slast > plan.side[0].bytes[t.src_rank])
@@ -343,12 +397,13 @@ void finish_stats(tpx_plan_s& plan) {
   s.bytes_read = s.bytes_written = s.bytes_fill = s.bytes_cross_rank = 0;
   for (const tpx_box& b : plan.boxes) {
     const uint64_t n = box_bytes(b);
-    s.bytes_written += n;
+    s.bytes_written += n * b.n_dst;
     if (b.kind == TPX_BOX_FILL) {
-      s.bytes_fill += n;
+      s.bytes_fill += n * b.n_dst;
     } else {
-      s.bytes_read += n;
-      if (b.src_rank != b.dst_rank) s.bytes_cross_rank += n;
+      s.bytes_read += n;  // a multicast move reads its source once
+      for (uint32_t k = 0; k < b.n_dst; ++k)
+        if (b.src_rank != b.dst_rank + k * b.dst_rank_stride) s.bytes_cross_rank += n;
     }
   }
 }

@@ -32,7 +32,8 @@ struct FlatBox {
   uint16_t src_rank, dst_rank;
   uint8_t kind;         // TPX_TILE_*
   uint8_t unit_log2;
-  uint8_t pad_[2];
+  uint8_t n_dst;            // the tile is written to buffers dst_rank + k * dst_rank_stride, k < n_dst
+  uint8_t dst_rank_stride;
 };
 static_assert(sizeof(FlatBox) == 80, "FlatBox layout");
 
@@ -74,6 +75,8 @@ TPX_HD tpx_tile tile_of(const FlatBox& b, uint32_t local) {
   t.dst_rank = b.dst_rank;
   t.kind = b.kind;
   t.unit_log2 = b.unit_log2;
+  t.n_dst = b.n_dst;
+  t.dst_rank_stride = b.dst_rank_stride;
   return t;
 }
 

@@ -16,12 +16,14 @@ def run_boxes(plan, src_bufs, dst_bufs, cover=None):
         for idx in np.ndindex(*ext) if ext else [()]:
             so = int(b.src_off) + sum(i * int(b.src_stride[k]) for k, i in enumerate(idx))
             do = int(b.dst_off) + sum(i * int(b.dst_stride[k]) for k, i in enumerate(idx))
-            if b.kind == B.BOX_FILL:
-                dst_bufs[b.dst_rank][do:do + run] = 0
-            else:
-                dst_bufs[b.dst_rank][do:do + run] = src_bufs[b.src_rank][so:so + run]
-            if cover is not None:
-                cover[b.dst_rank][do:do + run] += 1
+            for k in range(b.n_dst):
+                r = b.dst_rank + k * b.dst_rank_stride
+                if b.kind == B.BOX_FILL:
+                    dst_bufs[r][do:do + run] = 0
+                else:
+                    dst_bufs[r][do:do + run] = src_bufs[b.src_rank][so:so + run]
+                if cover is not None:
+                    cover[r][do:do + run] += 1
 
 
 def run_tiles(plan, src_bufs, dst_bufs, cover=None):
@@ -32,10 +34,12 @@ def run_tiles(plan, src_bufs, dst_bufs, cover=None):
         j = np.arange(t.run_units, dtype=np.int64)[None, :, None]
         k = np.arange(unit, dtype=np.int64)[None, None, :]
         di = (int(t.dst_off) + i * int(t.dst_pitch) + j * int(t.dst_step) + k).reshape(-1)
-        if t.kind == B.TILE_FILL:
-            dst_bufs[t.dst_rank][di] = 0
-        else:
-            si = (int(t.src_off) + i * int(t.src_pitch) + j * int(t.src_step) + k).reshape(-1)
-            dst_bufs[t.dst_rank][di] = src_bufs[t.src_rank][si]
-        if cover is not None:
-            np.add.at(cover[t.dst_rank], di, 1)
+        for c in range(t.n_dst):
+            r = t.dst_rank + c * t.dst_rank_stride
+            if t.kind == B.TILE_FILL:
+                dst_bufs[r][di] = 0
+            else:
+                si = (int(t.src_off) + i * int(t.src_pitch) + j * int(t.src_step) + k).reshape(-1)
+                dst_bufs[r][di] = src_bufs[t.src_rank][si]
+            if cover is not None:
+                np.add.at(cover[r], di, 1)

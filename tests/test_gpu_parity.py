@@ -211,3 +211,51 @@ def test_dataset_full_size(cuda):
     c = H.DATASET_CFG
     print("dataset full size", c, flush=True)
     _dataset_case(c["n_samples"], c["global_batch"], c["D_src"], c["D_dst"], c["steps_done"], c["seed"])
+
+
+# ---------------------------------------------------------------------------------------------
+# the paper's own reconfigurations (sections 6.2, 6.3, 6.6, 6.8) at full size
+# ---------------------------------------------------------------------------------------------
+def _paper_pairs():
+    import bench
+    return [k for k in bench.PAPER_PAIRS if not k.startswith("gpt6.7b") and not k.startswith("gpt2.7b_(4,2,1)->(4,4")]
+
+
+@pytest.mark.parametrize("name", _paper_pairs())
+def test_paper_reconfiguration_pairs(cuda, name):
+    """Data-, pipeline- and tensor-parallel changes, redeployment and the elastic-scaling sequence of the
+    paper's evaluation: every destination tensor equals its closed-form contents, gaps stay untouched, and
+    replicated destinations are written from a single read (multicast moves)."""
+    import bench
+    mk_, s_, d_, _, seed = bench.PAPER_PAIRS[name]
+    print("pair", name, flush=True)
+    model = Model(mk_["n_layers"], mk_["hidden"], mk_["n_heads"], mk_["ffn"], mk_["vocab_true"], mk_.get("max_pos", 1024),
+                  mk_.get("vocab_divisor", 0), tuple(mk_["state_elem_bytes"]))
+    src = Parallel(s_["T"], s_["P"], s_["D"], s_.get("stage_first_layer"))
+    dst = Parallel(d_["T"], d_["P"], d_["D"], d_.get("stage_first_layer"))
+    mix = synth.MIX_GPT
+    plan = plan_for(model, src, dst)
+    st = plan.stats()
+    if src.D == 1 and dst.D > 1 and src.T == dst.T and src.P == dst.P:
+        assert st["bytes_read"] * dst.D == st["bytes_written"]        # read once, written D' times
+    assert st["bytes_read"] <= st["bytes_written"]
+    src_gpu = []
+    for descs, n in H.manifest_descs(model, src):
+        b = G.alloc(n, H.SRC_GAP)
+        synth.fill_buffer(b, descs, seed, mix)
+        src_gpu.append(b)
+    got, _ = G.execute(plan, src_gpu)
+    torch.cuda.synchronize()
+    assert H.closed_form_mismatches(got, model, src, dst, seed, mix) == 0
+    for b, (descs, n) in zip(got, H.manifest_descs(model, dst)):
+        assert H.gaps_untouched(b, descs, H.POISON)
+    del got, src_gpu
+    torch.cuda.empty_cache()
+
+
+def test_multicast_small(cuda):
+    """Replicated destinations on odd-sized models: copy, fill and transposing tiles with several destinations."""
+    _check_small(SMALL, SMALL_MIX, Parallel(2, 2, 1), Parallel(2, 2, 3))
+    _check_small(ODD, ODD_MIX, Parallel(3, 1, 1), Parallel(4, 1, 2))
+    _check_small(SMALL, SMALL_MIX, Parallel(2, 1, 1), Parallel(3, 2, 2, w_transposed=1))
+    _check_small(WIDE, synth.MIX_GPT, Parallel(2, 1, 2), Parallel(4, 1, 4))

@@ -121,6 +121,11 @@ typedef struct {
 #define TPX_TILE_TRANSPOSE 2u /* unit = element; rows are contiguous on the source (src_step == unit),
                                  columns on the destination (dst_pitch == unit); staged through LDS */
 #define TPX_TILE_GATHER 3u    /* unit = element; arbitrary steps (degenerate transposes) */
+#define TPX_TILE_MERGE 4u     /* the merge of algorithm 1 done inside the tile: destination rows are written whole;
+                                 columns [k*seg_units, (k+1)*seg_units) of every row come from segment
+                                 seg_first + k (its own source buffer, offset and row pitch), k < n_seg;
+                                 src_off / src_pitch / src_rank are unused, src_off = first row of the tile
+                                 within the box (add src_off * segment pitch to the segment's offset) */
 typedef struct {
   uint64_t src_off, dst_off;  /* bytes, inside the rank buffers */
   uint64_t src_pitch, dst_pitch;
@@ -132,7 +137,19 @@ typedef struct {
   uint8_t  unit_log2;         /* 4 (16-byte vectors) when offsets, pitches and run length allow, else smaller */
   uint8_t  n_dst;             /* written to buffers dst_rank + k*dst_rank_stride, k < n_dst */
   uint8_t  dst_rank_stride;
+  uint32_t seg_first;         /* MERGE tiles: first segment, segments per row, units per segment */
+  uint32_t n_seg;
+  uint32_t seg_units;
+  uint32_t pad_;
 } tpx_tile;
+
+/* One source of a MERGE tile: the rows of a source sub-tensor piece. */
+typedef struct {
+  uint64_t src_off;           /* byte offset of row 0 of the box in buffer src_rank */
+  uint64_t src_pitch;         /* bytes between rows */
+  uint32_t src_rank;
+  uint32_t pad_;
+} tpx_segment;
 
 typedef struct {
   uint64_t n_pieces;          /* sub-tensor pieces produced by the split step */
@@ -172,6 +189,8 @@ uint64_t   tpx_num_boxes(const tpx_plan_t*);
 tpx_status tpx_get_box(const tpx_plan_t*, uint64_t i, tpx_box* out);
 uint64_t   tpx_num_tiles(const tpx_plan_t*);
 tpx_status tpx_get_tile(const tpx_plan_t*, uint64_t i, tpx_tile* out);
+uint64_t   tpx_num_segments(const tpx_plan_t*);
+tpx_status tpx_get_segment(const tpx_plan_t*, uint64_t i, tpx_segment* out);
 
 /* DEVICE bytes tpx_execute needs in `workspace` (the plan tables: flat boxes and tile prefix sums). */
 uint64_t   tpx_workspace_bytes(const tpx_plan_t*);
@@ -201,10 +220,10 @@ void tpx_free(tpx_plan_t*);
 const char* tpx_last_error(void);
 
 /* Global tuning knobs, read by later tpx_plan / tpx_execute calls on any thread:
- *   "tile_bytes"  upper bound of bytes per tile (power of two, 4096 .. 4194304; default 262144); small jobs
+ *   "tile_bytes"  upper bound of bytes per tile (power of two, 4096 .. 4194304; default 131072); small jobs
  *                 use smaller tiles, down to 16384, so that the launch still has thousands of workgroups
- *   "variant"     kernel variant, a bit field documented in the kernel source (default 12: 256 threads per
- *                 workgroup, four 16-byte loads in flight per thread, nontemporal loads and stores)
+ *   "variant"     kernel variant, a bit field documented in the kernel source (default 91: 1024 threads per
+ *                 workgroup, eight 16-byte loads in flight per thread, nontemporal loads and stores)
  * Errors: INVALID_ARG for an unknown key or a value out of range. */
 tpx_status tpx_set_option(const char* key, uint64_t value);
 

@@ -28,7 +28,7 @@ TPX_MAX_RANKS = 128
 SIDE_SRC, SIDE_DST = 0, 1
 MODEL_TIED_HEAD = 1
 BOX_COPY, BOX_FILL, BOX_TRANSPOSE = 0, 1, 2
-TILE_COPY, TILE_FILL, TILE_TRANSPOSE, TILE_GATHER = 0, 1, 2, 3
+TILE_COPY, TILE_FILL, TILE_TRANSPOSE, TILE_GATHER, TILE_MERGE = 0, 1, 2, 3, 4
 
 
 class TpxError(RuntimeError):
@@ -69,7 +69,12 @@ class tpx_tile(C.Structure):
                 ("dst_pitch", C.c_uint64), ("src_step", C.c_uint64), ("dst_step", C.c_uint64),
                 ("run_units", C.c_uint32), ("nrows", C.c_uint32), ("src_rank", C.c_uint16),
                 ("dst_rank", C.c_uint16), ("kind", C.c_uint8), ("unit_log2", C.c_uint8), ("n_dst", C.c_uint8),
-                ("dst_rank_stride", C.c_uint8)]
+                ("dst_rank_stride", C.c_uint8), ("seg_first", C.c_uint32), ("n_seg", C.c_uint32),
+                ("seg_units", C.c_uint32), ("pad_", C.c_uint32)]
+
+
+class tpx_segment(C.Structure):
+    _fields_ = [("src_off", C.c_uint64), ("src_pitch", C.c_uint64), ("src_rank", C.c_uint32), ("pad_", C.c_uint32)]
 
 
 class tpx_stats_t(C.Structure):
@@ -77,7 +82,7 @@ class tpx_stats_t(C.Structure):
                                           "bytes_fill", "bytes_cross_rank", "plan_ns")]
 
 
-assert C.sizeof(tpx_tile) == 64
+assert C.sizeof(tpx_tile) == 80
 
 _P = C.c_void_p
 _sigs = {
@@ -94,6 +99,8 @@ _sigs = {
     "tpx_get_box": (C.c_int, [_P, C.c_uint64, C.POINTER(tpx_box)]),
     "tpx_num_tiles": (C.c_uint64, [_P]),
     "tpx_get_tile": (C.c_int, [_P, C.c_uint64, C.POINTER(tpx_tile)]),
+    "tpx_num_segments": (C.c_uint64, [_P]),
+    "tpx_get_segment": (C.c_int, [_P, C.c_uint64, C.POINTER(tpx_segment)]),
     "tpx_workspace_bytes": (C.c_uint64, [_P]),
     "tpx_execute": (C.c_int, [_P, C.POINTER(_P), C.POINTER(_P), _P, _P]),
     "tpx_prepare": (C.c_int, [_P, _P, _P]),
@@ -190,6 +197,14 @@ class Plan:
             t = tpx_tile()
             _check(_lib.tpx_get_tile(self._h, i, C.byref(t)))
             out.append(t)
+        return out
+
+    def segments(self) -> list:
+        out = []
+        for i in range(_lib.tpx_num_segments(self._h)):
+            g = tpx_segment()
+            _check(_lib.tpx_get_segment(self._h, i, C.byref(g)))
+            out.append(g)
         return out
 
     def workspace_bytes(self) -> int:

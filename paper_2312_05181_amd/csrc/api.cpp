@@ -112,6 +112,14 @@ tpx_status tpx_get_tile(const tpx_plan_t* p, uint64_t i, tpx_tile* out) {
   return TPX_OK;
 }
 
+uint64_t tpx_num_segments(const tpx_plan_t* p) { return p ? p->segments.size() : 0; }
+
+tpx_status tpx_get_segment(const tpx_plan_t* p, uint64_t i, tpx_segment* out) {
+  if (!p || !out || i >= p->segments.size()) return fail(TPX_ERR_INVALID_ARG, "tpx_get_segment: bad argument");
+  *out = p->segments[i];
+  return TPX_OK;
+}
+
 uint64_t tpx_workspace_bytes(const tpx_plan_t* p) { return p ? workspace_layout(*p).total : 0; }
 
 tpx_status tpx_prepare(tpx_plan_t* p, void* workspace, void* hip_stream) {
@@ -158,7 +166,8 @@ tpx_status tpx_set_option(const char* key, uint64_t value) {
     return TPX_OK;
   }
   if (!std::strcmp(key, "variant")) {
-    if (value > 47) return fail(TPX_ERR_INVALID_ARG, "variant out of range");
+    if (value > 95 || (value & 7) < 2 || (value & 7) > 4 || (((value >> 3) & 1) != ((value >> 4) & 1)))
+      return fail(TPX_ERR_INVALID_ARG, "variant out of range");
     tuning().variant = value;
     return TPX_OK;
   }

@@ -50,57 +50,67 @@ struct DstSet {
   __device__ __forceinline__ uint8_t* base(uint32_t c) const { return table[rank + c * stride] + off; }
 };
 
-// Copy (or zero-fill) nrows rows of run_units units of type V.  Consecutive threads take consecutive
-// units of the row-major unit index space, so accesses are coalesced along each row on both sides.
-// MC: the loaded units are stored to every destination of the set (read once, write many).
+// The common loop: unit idx (0 <= idx < total) is loaded from src_of(idx) and stored at byte offset
+// dst_off_of(idx) of every destination.  Consecutive threads take consecutive units; every thread keeps U
+// independent loads in flight before storing them; the ragged end is one more, predicated, block of U.
+template <typename V, int kThreads, int U, bool NTL, bool NTS, bool FILL, bool MC, typename SrcOf, typename DstOffOf>
+__device__ __forceinline__ void move_units(uint32_t total, const DstSet& ds, SrcOf src_of, DstOffOf dst_off_of) {
+  const uint32_t n_dst = MC ? ds.n : 1;
+  uint8_t* const d0 = ds.base(0);
+  uint32_t i = threadIdx.x;
+  for (; i + (U - 1) * kThreads < total; i += U * kThreads) {
+    V r[U];
+    uint64_t doff[U];
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+      r[k] = FILL ? zero_of<V>() : ld<V, NTL>(src_of(i + k * kThreads));
+      doff[k] = dst_off_of(i + k * kThreads);
+    }
+    for (uint32_t c = 0; c < n_dst; ++c) {
+      uint8_t* d = MC ? ds.base(c) : d0;
+#pragma unroll
+      for (int k = 0; k < U; ++k) st<V, NTS>(reinterpret_cast<V*>(d + doff[k]), r[k]);
+    }
+  }
+  if (i < total) {
+    V r[U];
+    uint64_t doff[U];
+#pragma unroll
+    for (int k = 0; k < U; ++k)
+      if (i + k * kThreads < total) {
+        r[k] = FILL ? zero_of<V>() : ld<V, NTL>(src_of(i + k * kThreads));
+        doff[k] = dst_off_of(i + k * kThreads);
+      }
+    for (uint32_t c = 0; c < n_dst; ++c) {
+      uint8_t* d = MC ? ds.base(c) : d0;
+#pragma unroll
+      for (int k = 0; k < U; ++k)
+        if (i + k * kThreads < total) st<V, NTS>(reinterpret_cast<V*>(d + doff[k]), r[k]);
+    }
+  }
+}
+
+// Copy (or zero-fill) nrows rows of run_units units of type V; rows are contiguous on both sides, so
+// accesses are coalesced along each row.  MC: every unit is stored to every destination of the set.
 template <typename V, int kThreads, int U, bool NTL, bool NTS, bool FILL, bool MC>
 __device__ __forceinline__ void move_rows(const uint8_t* __restrict__ s, const DstSet& ds, uint32_t run_units,
                                           uint32_t nrows, uint64_t sp, uint64_t dp) {
   const uint32_t total = run_units * nrows;
-  const uint32_t n_dst = MC ? ds.n : 1;
-  uint8_t* const d0 = ds.base(0);
-  uint32_t i = threadIdx.x;
   if (nrows == 1) {
-    const V* sv = reinterpret_cast<const V*>(s);
-    for (; i + (U - 1) * kThreads < total; i += U * kThreads) {
-      V r[U];
-#pragma unroll
-      for (int k = 0; k < U; ++k) r[k] = FILL ? zero_of<V>() : ld<V, NTL>(sv + i + k * kThreads);
-      for (uint32_t c = 0; c < n_dst; ++c) {
-        V* dv = reinterpret_cast<V*>(MC ? ds.base(c) : d0);
-#pragma unroll
-        for (int k = 0; k < U; ++k) st<V, NTS>(dv + i + k * kThreads, r[k]);
-      }
-    }
-    for (; i < total; i += kThreads) {
-      const V v = FILL ? zero_of<V>() : ld<V, NTL>(sv + i);
-      for (uint32_t c = 0; c < n_dst; ++c) st<V, NTS>(reinterpret_cast<V*>(MC ? ds.base(c) : d0) + i, v);
-    }
+    move_units<V, kThreads, U, NTL, NTS, FILL, MC>(
+        total, ds, [&](uint32_t idx) { return reinterpret_cast<const V*>(s) + idx; },
+        [&](uint32_t idx) { return uint64_t(idx) * sizeof(V); });
   } else {
-    for (; i + (U - 1) * kThreads < total; i += U * kThreads) {
-      V r[U];
-      uint64_t doff[U];
-#pragma unroll
-      for (int k = 0; k < U; ++k) {
-        const uint32_t idx = i + k * kThreads;
-        const uint32_t row = idx / run_units;
-        const uint32_t col = idx - row * run_units;
-        doff[k] = row * dp + uint64_t(col) * sizeof(V);
-        r[k] = FILL ? zero_of<V>() : ld<V, NTL>(reinterpret_cast<const V*>(s + row * sp + uint64_t(col) * sizeof(V)));
-      }
-      for (uint32_t c = 0; c < n_dst; ++c) {
-        uint8_t* d = MC ? ds.base(c) : d0;
-#pragma unroll
-        for (int k = 0; k < U; ++k) st<V, NTS>(reinterpret_cast<V*>(d + doff[k]), r[k]);
-      }
-    }
-    for (; i < total; i += kThreads) {
-      const uint32_t row = i / run_units;
-      const uint32_t col = i - row * run_units;
-      const V v = FILL ? zero_of<V>() : ld<V, NTL>(reinterpret_cast<const V*>(s + row * sp + uint64_t(col) * sizeof(V)));
-      for (uint32_t c = 0; c < n_dst; ++c)
-        st<V, NTS>(reinterpret_cast<V*>((MC ? ds.base(c) : d0) + row * dp + uint64_t(col) * sizeof(V)), v);
-    }
+    move_units<V, kThreads, U, NTL, NTS, FILL, MC>(
+        total, ds,
+        [&](uint32_t idx) {
+          const uint32_t row = idx / run_units;
+          return reinterpret_cast<const V*>(s + row * sp + uint64_t(idx - row * run_units) * sizeof(V));
+        },
+        [&](uint32_t idx) {
+          const uint32_t row = idx / run_units;
+          return row * dp + uint64_t(idx - row * run_units) * sizeof(V);
+        });
   }
 }
 
@@ -114,6 +124,48 @@ __device__ __forceinline__ void move_rows_any(uint32_t unit_log2, const uint8_t*
     case 1: move_rows<uint16_t, kThreads, 2, false, false, FILL, MC>(s, ds, run_units, nrows, sp, dp); break;
     default: move_rows<uint8_t, kThreads, 2, false, false, FILL, MC>(s, ds, run_units, nrows, sp, dp); break;
   }
+}
+
+// Merge tile: whole destination rows of row_units 16-byte units are written contiguously; columns
+// [g*seg_units, (g+1)*seg_units) of every row are read from segment g.  The per-segment source row
+// pointers are staged in LDS (a few hundred bytes) because lanes of one wave may read different segments.
+struct SegLds {
+  const uint8_t* base;  // first row of this tile in the segment's source
+  uint64_t pitch;
+};
+constexpr uint32_t kMaxSegLds = 64;
+
+template <int kThreads, int U, bool NTL, bool NTS>
+__device__ __forceinline__ void merge_tile(const tpx_tile& t, const tpx_segment* __restrict__ segs, const uint8_t* const* src_table,
+                                           const DstSet& ds, SegLds* lseg) {
+  const uint32_t row_units = t.run_units, seg_units = t.seg_units, n_seg = t.n_seg;
+  const bool in_lds = n_seg <= kMaxSegLds;
+  if (in_lds) {
+    for (uint32_t g = threadIdx.x; g < n_seg; g += kThreads) {
+      const tpx_segment sg = segs[t.seg_first + g];
+      lseg[g].base = src_table[sg.src_rank] + sg.src_off + t.src_off * sg.src_pitch;  // t.src_off = first row
+      lseg[g].pitch = sg.src_pitch;
+    }
+    __syncthreads();
+  }
+  auto src_of = [&](uint32_t idx) -> const v4u* {
+    const uint32_t row = idx / row_units;
+    const uint32_t c = idx - row * row_units;
+    const uint32_t g = c / seg_units;
+    const uint32_t col = c - g * seg_units;
+    if (in_lds) return reinterpret_cast<const v4u*>(lseg[g].base + row * lseg[g].pitch + uint64_t(col) * 16);
+    const tpx_segment sg = segs[t.seg_first + g];
+    return reinterpret_cast<const v4u*>(src_table[sg.src_rank] + sg.src_off + (t.src_off + row) * sg.src_pitch + uint64_t(col) * 16);
+  };
+  const uint32_t total = row_units * t.nrows;
+  const bool dense = t.dst_pitch == uint64_t(row_units) * 16;  // rows adjacent in the destination
+  auto dst_off = [&](uint32_t idx) -> uint64_t {
+    if (dense) return uint64_t(idx) * 16;
+    const uint32_t row = idx / row_units;
+    return row * t.dst_pitch + uint64_t(idx - row * row_units) * 16;
+  };
+  if (ds.n > 1) move_units<v4u, kThreads, U, NTL, NTS, false, true>(total, ds, src_of, dst_off);
+  else move_units<v4u, kThreads, U, NTL, NTS, false, false>(total, ds, src_of, dst_off);
 }
 
 // Transposing tile: element (i, j) is contiguous in j on the source and in i on the destination.
@@ -154,9 +206,11 @@ constexpr int kLdsBytes = 64 * 65 * 4;  // largest transposing sub-tile
 template <int kThreads, int U, bool NTL, bool NTS>
 __global__ __launch_bounds__(kThreads) void tpx_execute_tiles(const tpx::FlatBox* __restrict__ boxes,
                                                               const uint32_t* __restrict__ first_tile,
-                                                              const uint32_t* __restrict__ coarse, uint32_t n_boxes,
+                                                              const uint32_t* __restrict__ coarse,
+                                                              const tpx_segment* __restrict__ segs, uint32_t n_boxes,
                                                               PtrTable ptrs) {
   extern __shared__ __align__(16) uint8_t lds_raw[];
+  __shared__ SegLds lseg[kMaxSegLds];
   // locate this workgroup's tile: uniform for the whole workgroup, so these are scalar loads
   const uint32_t box = tpx::find_box(first_tile, coarse, n_boxes, blockIdx.x);
   const tpx::FlatBox fb = boxes[box];
@@ -166,6 +220,10 @@ __global__ __launch_bounds__(kThreads) void tpx_execute_tiles(const tpx::FlatBox
   if (t.kind == TPX_TILE_FILL) {
     if (mc) move_rows_any<kThreads, U, NTL, NTS, true, true>(t.unit_log2, nullptr, ds, t.run_units, t.nrows, 0, t.dst_pitch);
     else move_rows_any<kThreads, U, NTL, NTS, true, false>(t.unit_log2, nullptr, ds, t.run_units, t.nrows, 0, t.dst_pitch);
+    return;
+  }
+  if (t.kind == TPX_TILE_MERGE) {
+    merge_tile<kThreads, U, NTL, NTS>(t, segs, ptrs.src, ds, lseg);
     return;
   }
   const uint8_t* s = ptrs.src[t.src_rank] + t.src_off;
@@ -214,32 +272,31 @@ tpx_status hip_fail(hipError_t e, const char* what) {
   return tpx::fail(TPX_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
 }
 
-using KernelFn = void (*)(const tpx::FlatBox*, const uint32_t*, const uint32_t*, uint32_t, PtrTable);
+using KernelFn = void (*)(const tpx::FlatBox*, const uint32_t*, const uint32_t*, const tpx_segment*, uint32_t, PtrTable);
 
 template <int T, int U>
-KernelFn pick_nt(bool ntl, bool nts) {
-  if (ntl) return nts ? tpx_execute_tiles<T, U, true, true> : tpx_execute_tiles<T, U, true, false>;
-  return nts ? tpx_execute_tiles<T, U, false, true> : tpx_execute_tiles<T, U, false, false>;
+KernelFn pick_nt(bool nt) {
+  return nt ? tpx_execute_tiles<T, U, true, true> : tpx_execute_tiles<T, U, false, false>;
 }
 
 template <int T>
 KernelFn pick_unroll(uint64_t variant) {
-  const bool ntl = (variant >> 2) & 1, nts = (variant >> 3) & 1;
-  switch (variant & 3) {
-    case 1: return pick_nt<T, 8>(ntl, nts);
-    case 2: return pick_nt<T, 2>(ntl, nts);
-    case 3: return pick_nt<T, 1>(ntl, nts);
-    default: return pick_nt<T, 4>(ntl, nts);
+  const bool nt = (variant >> 3) & 1;
+  switch (variant & 7) {
+    case 2: return pick_nt<T, 4>(nt);
+    case 4: return pick_nt<T, 16>(nt);
+    default: return pick_nt<T, 8>(nt);
   }
 }
 
-// variant bits: [1:0] loads in flight per thread (0: 4, 1: 8, 2: 2, 3: 1); bit 2: nontemporal loads;
-// bit 3: nontemporal stores; bits [5:4] threads per workgroup (0: 256, 1: 1024, 2: 512).
+// variant bits: [2:0] log2 of the 16-byte loads in flight per thread (2, 3 or 4); bits 3 and 4 (set
+// together or not at all): nontemporal loads and stores; bits [6:5] threads per workgroup (0: 256, 1: 512,
+// 2: 1024).
 int threads_of(uint64_t variant) {
-  switch ((variant >> 4) & 3) {
-    case 1: return 1024;
-    case 2: return 512;
-    default: return 256;
+  switch ((variant >> 5) & 3) {
+    case 0: return 256;
+    case 1: return 512;
+    default: return 1024;
   }
 }
 
@@ -261,7 +318,8 @@ WorkspaceLayout workspace_layout(const tpx_plan_s& plan) {
   w.boxes_off = 0;
   w.first_off = up(plan.flat.size() * sizeof(FlatBox));
   w.coarse_off = w.first_off + up(plan.first_tile.size() * sizeof(uint32_t));
-  w.total = std::max<uint64_t>(256, w.coarse_off + up(plan.coarse.size() * sizeof(uint32_t)));
+  w.seg_off = w.coarse_off + up(plan.coarse.size() * sizeof(uint32_t));
+  w.total = std::max<uint64_t>(256, w.seg_off + up(plan.segments.size() * sizeof(tpx_segment)));
   return w;
 }
 
@@ -274,6 +332,8 @@ tpx_status hip_upload_tables(void* workspace, const tpx_plan_s& plan, void* stre
     e = hipMemcpyAsync(base + w.first_off, plan.first_tile.data(), plan.first_tile.size() * sizeof(uint32_t), hipMemcpyHostToDevice, st);
   if (e == hipSuccess)
     e = hipMemcpyAsync(base + w.coarse_off, plan.coarse.data(), plan.coarse.size() * sizeof(uint32_t), hipMemcpyHostToDevice, st);
+  if (e == hipSuccess && !plan.segments.empty())
+    e = hipMemcpyAsync(base + w.seg_off, plan.segments.data(), plan.segments.size() * sizeof(tpx_segment), hipMemcpyHostToDevice, st);
   if (e != hipSuccess) return hip_fail(e, "copying the plan tables to the workspace");
   e = hipStreamSynchronize(st);
   if (e != hipSuccess) return hip_fail(e, "waiting for the plan table copy");
@@ -296,7 +356,8 @@ tpx_status hip_launch_tiles(const void* workspace, const tpx_plan_s& plan, const
   hipLaunchKernelGGL(k, dim3(uint32_t(plan.n_tiles)), dim3(threads_of(variant)), plan.needs_lds ? kLdsBytes : 0,
                      static_cast<hipStream_t>(stream), reinterpret_cast<const FlatBox*>(base + w.boxes_off),
                      reinterpret_cast<const uint32_t*>(base + w.first_off),
-                     reinterpret_cast<const uint32_t*>(base + w.coarse_off), uint32_t(plan.flat.size()), pt);
+                     reinterpret_cast<const uint32_t*>(base + w.coarse_off),
+                     reinterpret_cast<const tpx_segment*>(base + w.seg_off), uint32_t(plan.flat.size()), pt);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(e, "launching the tile kernel");
   return TPX_OK;

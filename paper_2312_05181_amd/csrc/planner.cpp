@@ -264,8 +264,54 @@ tpx_status tile_boxes(tpx_plan_s& plan, uint64_t tile_bytes) {
   for (const tpx_box& b : plan.boxes) total += box_bytes(b);
   while (tile_bytes > 16384 && total / tile_bytes < 8192) tile_bytes >>= 1;
   plan.tile_bytes_used = tile_bytes;
-  for (const tpx_box& b : plan.boxes) {
+  plan.segments.clear();
+  for (size_t bi = 0; bi < plan.boxes.size(); ++bi) {
+    const tpx_box& b = plan.boxes[bi];
     if (box_bytes(b) == 0) continue;
+    // merge(W) inside the tile: K consecutive moves that each bring one column block of the same
+    // destination rows (equal widths, together the whole row) become one MERGE box whose tiles write
+    // whole destination rows and read K sources.  Anything irregular keeps one box per move.
+    if (b.kind == TPX_BOX_COPY && b.ndim == 1 && b.run_bytes % 16 == 0 && b.dst_stride[0] % b.run_bytes == 0 &&
+        b.dst_stride[0] > b.run_bytes && b.dst_stride[0] <= tile_bytes && b.extent[0] <= 0xffffffffull) {
+      const uint64_t K = b.dst_stride[0] / b.run_bytes;
+      bool ok = bi + K <= plan.boxes.size() && K <= 0xffff;
+      uint64_t bits = b.dst_off | b.dst_stride[0];
+      for (uint64_t k = 0; ok && k < K; ++k) {
+        const tpx_box& c = plan.boxes[bi + k];
+        ok = c.kind == TPX_BOX_COPY && c.ndim == 1 && c.run_bytes == b.run_bytes && c.extent[0] == b.extent[0] &&
+             c.dst_stride[0] == b.dst_stride[0] && c.dst_rank == b.dst_rank && c.n_dst == b.n_dst &&
+             c.dst_rank_stride == b.dst_rank_stride && c.dst_off == b.dst_off + k * b.run_bytes &&
+             c.src_rank < TPX_MAX_RANKS;
+        bits |= c.src_off | c.src_stride[0];
+      }
+      if (ok && bits % 16 == 0) {
+        FlatBox f{};
+        f.kind = TPX_TILE_MERGE;
+        f.unit_log2 = 4;
+        f.dst_rank = uint16_t(b.dst_rank);
+        f.n_dst = uint8_t(b.n_dst);
+        f.dst_rank_stride = uint8_t(b.dst_rank_stride);
+        if (b.dst_rank + uint64_t(b.n_dst - 1) * b.dst_rank_stride >= TPX_MAX_RANKS) return fail(TPX_ERR_INVALID_ARG, "rank out of range");
+        f.dst_off = b.dst_off;
+        f.dst_pitch = b.dst_stride[0];
+        f.src_step = f.dst_step = 16;
+        f.nrows = uint32_t(b.extent[0]);
+        f.run_units = uint32_t(b.dst_stride[0] / 16);
+        f.chunk_units = f.run_units;
+        f.chunks_per_row = 1;
+        f.rows_per_tile = uint32_t(std::max<uint64_t>(1, tile_bytes / b.dst_stride[0]));
+        f.seg_first = uint32_t(plan.segments.size());
+        f.n_seg = uint32_t(K);
+        f.seg_units = uint32_t(b.run_bytes / 16);
+        for (uint64_t k = 0; k < K; ++k) {
+          const tpx_box& c = plan.boxes[bi + k];
+          plan.segments.push_back(tpx_segment{c.src_off, c.src_stride[0], c.src_rank, 0});
+        }
+        plan.flat.push_back(f);
+        bi += K - 1;
+        continue;
+      }
+    }
     if (b.src_rank >= TPX_MAX_RANKS || b.dst_rank >= TPX_MAX_RANKS) return fail(TPX_ERR_INVALID_ARG, "rank out of range");
     FlatBox f{};
     f.src_rank = uint16_t(b.src_rank);
@@ -380,7 +426,16 @@ tpx_status validate_tiles(tpx_plan_s& plan) {
       if (r >= plan.side[1].bytes.size() || dlast > plan.side[1].bytes[r])
         return fail(TPX_ERR_INVALID_ARG, "internal: a move writes outside its destination buffer");
     }
-    if (t.kind != TPX_TILE_FILL) {
+    if (t.kind == TPX_TILE_MERGE) {
+      if (!t.n_seg || uint64_t(t.n_seg) * t.seg_units != t.run_units || uint64_t(t.seg_first) + t.n_seg > plan.segments.size())
+        return fail(TPX_ERR_INVALID_ARG, "internal: bad segment range");
+      for (uint32_t k = 0; k < t.n_seg; ++k) {
+        const tpx_segment& sg = plan.segments[t.seg_first + k];
+        const uint64_t slast = sg.src_off + (t.nrows - 1) * sg.src_pitch + uint64_t(t.seg_units) * unit;
+        if (sg.src_rank >= plan.side[0].bytes.size() || slast > plan.side[0].bytes[sg.src_rank])
+          return fail(TPX_ERR_INVALID_ARG, "internal: a merge reads outside its source buffer");
+      }
+    } else if (t.kind != TPX_TILE_FILL) {
       const uint64_t slast = t.src_off + (t.nrows - 1) * t.src_pitch + (t.run_units - 1) * t.src_step + unit;
       if (t.src_rank >= plan.side[0].bytes.size() || slast > plan.side[0].bytes[t.src_rank])
         return fail(TPX_ERR_INVALID_ARG, "internal: a move reads outside its source buffer");

@@ -34,8 +34,12 @@ struct FlatBox {
   uint8_t unit_log2;
   uint8_t n_dst;            // the tile is written to buffers dst_rank + k * dst_rank_stride, k < n_dst
   uint8_t dst_rank_stride;
+  uint32_t seg_first;       // MERGE boxes: first entry in the segment table, segments per row,
+  uint32_t n_seg;           // units per segment
+  uint32_t seg_units;
+  uint32_t pad_;
 };
-static_assert(sizeof(FlatBox) == 80, "FlatBox layout");
+static_assert(sizeof(FlatBox) == 96, "FlatBox layout");
 
 constexpr uint32_t kCoarseShift = 6;  // one coarse entry per 64 tiles
 
@@ -77,6 +81,10 @@ TPX_HD tpx_tile tile_of(const FlatBox& b, uint32_t local) {
   t.unit_log2 = b.unit_log2;
   t.n_dst = b.n_dst;
   t.dst_rank_stride = b.dst_rank_stride;
+  t.seg_first = b.seg_first;
+  t.n_seg = b.n_seg;
+  t.seg_units = b.seg_units;
+  if (b.kind == TPX_TILE_MERGE) t.src_off = row0;  // sources are per segment; the tile only needs its first row
   return t;
 }
 

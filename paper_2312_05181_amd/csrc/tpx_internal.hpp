@@ -54,8 +54,8 @@ tpx_status sigma_of(const tpx_model& m, const tpx_parallel& par, uint32_t name, 
 tpx_status build_side(const tpx_model& m, const tpx_parallel& par, Side& out);
 
 struct Tuning {
-  uint64_t tile_bytes = 262144;
-  uint64_t variant = 12;  // 256 threads, 4 loads in flight, nontemporal loads and stores
+  uint64_t tile_bytes = 131072;
+  uint64_t variant = 91;  // 1024 threads, 8 loads in flight per thread, nontemporal loads and stores
 };
 Tuning& tuning();
 
@@ -67,6 +67,7 @@ struct tpx_plan_s {
   tpx::Side side[2];
   std::vector<tpx_box> boxes;
   std::vector<tpx::FlatBox> flat;     // what the GPU executes
+  std::vector<tpx_segment> segments;  // sources of MERGE boxes
   std::vector<uint32_t> first_tile;   // flat.size() + 1 prefix sums of tiles
   std::vector<uint32_t> coarse;       // box index of every 64th tile (+ sentinel)
   uint64_t n_tiles = 0;
@@ -89,9 +90,9 @@ tpx_status plan_dataset_moves(tpx_plan_s& plan, uint64_t n_samples, uint32_t B, 
                               std::vector<uint64_t>& dst_cursors);
 
 // HIP executor (kernels.hip).
-// Workspace layout: flat boxes, then first_tile, then coarse, each section starting on a 256-byte boundary.
+// Workspace layout: flat boxes, then first_tile, then coarse, then segments, each section starting on a 256-byte boundary.
 struct WorkspaceLayout {
-  uint64_t boxes_off = 0, first_off = 0, coarse_off = 0, total = 0;
+  uint64_t boxes_off = 0, first_off = 0, coarse_off = 0, seg_off = 0, total = 0;
 };
 WorkspaceLayout workspace_layout(const tpx_plan_s& plan);
 tpx_status hip_upload_tables(void* workspace, const tpx_plan_s& plan, void* stream);

@@ -28,8 +28,26 @@ def run_boxes(plan, src_bufs, dst_bufs, cover=None):
 
 def run_tiles(plan, src_bufs, dst_bufs, cover=None):
     """Apply every tile, unit by unit, exactly as the tile table defines it."""
+    segs = plan.segments()
     for t in plan.tiles():
         unit = 1 << t.unit_log2
+        if t.kind == B.TILE_MERGE:
+            # whole destination rows; column block k of every row comes from segment seg_first + k
+            row0 = int(t.src_off)
+            i = np.arange(t.nrows, dtype=np.int64)[:, None, None]
+            j = np.arange(t.seg_units, dtype=np.int64)[None, :, None]
+            kk = np.arange(unit, dtype=np.int64)[None, None, :]
+            assert t.n_seg * t.seg_units == t.run_units
+            for c in range(t.n_dst):
+                r = t.dst_rank + c * t.dst_rank_stride
+                for g in range(t.n_seg):
+                    sg = segs[t.seg_first + g]
+                    si = (int(sg.src_off) + (row0 + i) * int(sg.src_pitch) + j * unit + kk).reshape(-1)
+                    di = (int(t.dst_off) + i * int(t.dst_pitch) + (g * t.seg_units + j) * unit + kk).reshape(-1)
+                    dst_bufs[r][di] = src_bufs[sg.src_rank][si]
+                    if cover is not None:
+                        np.add.at(cover[r], di, 1)
+            continue
         i = np.arange(t.nrows, dtype=np.int64)[:, None, None]
         j = np.arange(t.run_units, dtype=np.int64)[None, :, None]
         k = np.arange(unit, dtype=np.int64)[None, None, :]

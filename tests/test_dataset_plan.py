@@ -21,7 +21,7 @@ def _run(n, Bsz, D, D2, s, eb=8, how="boxes"):
     try:
         plan = tpx.tpx_plan_dataset(n, Bsz, D, D2, cur, index_elem_bytes=eb)
     finally:
-        tpx.tpx_set_option("tile_bytes", 262144)
+        tpx.tpx_set_option("tile_bytes", 131072)
     assert plan.dst_cursors == want_cur
     assert [plan.buffer_bytes(0, j) for j in range(D)] == [p.nbytes for p in parts]
     assert [plan.buffer_bytes(1, j) for j in range(D2)] == [p.nbytes for p in want_parts]

@@ -54,10 +54,10 @@ def test_several_tiles_and_ragged_tails(cuda, tile_bytes, src, dst):
         plan = _check_small(WIDE, synth.MIX_GPT, src, dst)
         assert plan.num_tiles() > 100
     finally:
-        tpx.tpx_set_option("tile_bytes", 262144)
+        tpx.tpx_set_option("tile_bytes", 131072)
 
 
-@pytest.mark.parametrize("variant", range(48))
+@pytest.mark.parametrize("variant", [u | (n * 24) | (t << 5) for t in range(3) for n in range(2) for u in (2, 3, 4)])
 def test_every_kernel_variant(cuda, variant):
     print("variant", variant, flush=True)
     tpx.tpx_set_option("variant", variant)
@@ -66,8 +66,8 @@ def test_every_kernel_variant(cuda, variant):
         _check_small(WIDE, synth.MIX_GPT, Parallel(4, 1, 1), Parallel(2, 2, 1))
         _check_small(ODD, ODD_MIX, Parallel(3, 1, 1), Parallel(4, 1, 1))
     finally:
-        tpx.tpx_set_option("variant", 12)
-        tpx.tpx_set_option("tile_bytes", 262144)
+        tpx.tpx_set_option("variant", 91)
+        tpx.tpx_set_option("tile_bytes", 131072)
 
 
 def test_tiny_config_and_layout_change(cuda):

@@ -106,7 +106,7 @@ def test_plan_interpreted_on_cpu_matches_oracle(model, mix, src, dst, how):
     try:
         plan = plan_for(model, src, dst)
     finally:
-        tpx.tpx_set_option("tile_bytes", 262144)
+        tpx.tpx_set_option("tile_bytes", 131072)
     got = [np.full(plan.buffer_bytes(1, r), H.POISON, dtype=np.uint8) for r in range(dst.n_ranks)]
     cover = [np.zeros(len(g), dtype=np.int32) for g in got]
     (host_exec.run_boxes if how == "boxes" else host_exec.run_tiles)(plan, src_bufs, got, cover)
@@ -294,7 +294,28 @@ def test_tiles_are_bounded_and_vector_aligned_on_the_headline_workload():
     for i in range(0, plan.num_tiles(), 997):
         t = B.tpx_tile()
         B._check(B._lib.tpx_get_tile(plan._h, i, t))
-        assert t.unit_log2 == 4 and t.kind == B.TILE_COPY
-        assert t.nrows * t.run_units * 16 <= 262144
+        assert t.unit_log2 == 4 and t.kind in (B.TILE_COPY, B.TILE_MERGE)
+        assert t.nrows * t.run_units * 16 <= 131072
         total += 1
     assert total > 300
+
+
+def test_row_parallel_merges_become_merge_tiles():
+    """T 8 -> 1: every row-parallel weight (attention projection, MLP down-projection) is merged from 8 column
+    blocks; its tiles write whole destination rows and read 8 segments (merge of algorithm 1, inside the tile)."""
+    model, src, dst, _, _ = H.CONFIGS[4]
+    plan = plan_for(model, src, dst)
+    segs = plan.segments()
+    assert len(segs) == model.n_layers * len(model.state_elem_bytes) * 2 * 8
+    assert sorted({g.src_rank for g in segs}) == list(range(8))
+    merge_bytes = 0
+    for i in range(0, plan.num_tiles(), 101):
+        t = B.tpx_tile()
+        B._check(B._lib.tpx_get_tile(plan._h, i, t))
+        if t.kind == B.TILE_MERGE:
+            assert t.n_seg == 8 and t.n_seg * t.seg_units == t.run_units and t.dst_pitch == t.run_units * 16
+            merge_bytes += 1
+    assert merge_bytes > 500
+    # a 3 -> 4 re-slicing has unequal pieces per destination row: those stay one tile per move
+    model5, src5, dst5, _, _ = H.CONFIGS[5]
+    assert len(plan_for(model5, src5, dst5).segments()) == 0

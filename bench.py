@@ -61,6 +61,13 @@ for _a, _b in (((1, 1, 4), (1, 1, 8)), ((1, 4, 1), (1, 8, 1)), ((4, 1, 1), (8, 1
     PAPER_PAIRS[f"bert-large_{_a}->{_b}".replace(" ", "")] = (_BERT, _c(*_a), _c(*_b), "gpt", 17)
     PAPER_PAIRS[f"bert-large_{_b}->{_a}".replace(" ", "")] = (_BERT, _c(*_b), _c(*_a), "gpt", 18)
 WORKLOADS.update(PAPER_PAIRS)
+# layout-changing reshards: fused-QKV order and transposed ([in, out]) weight storage on the destination
+LAYOUT_PAIRS = {
+    "gpt1.3b_(4,2,1)->(2,4,1)_qkv_major_dst": (_G13, _c(4, 2, 1), _c(2, 4, 1, qkv_layout=1), "gpt", 21),
+    "gpt1.3b_(4,2,1)->(2,4,1)_transposed_dst": (_G13, _c(4, 2, 1), _c(2, 4, 1, w_transposed=1), "gpt", 22),
+    "gpt1.3b_(4,2,1)->(4,2,1)_transposed_dst": (_G13, _c(4, 2, 1), _c(4, 2, 1, w_transposed=1), "gpt", 23),
+}
+WORKLOADS.update(LAYOUT_PAIRS)
 DEFAULT_WORKLOAD = "gpt6.7b_(8,1,1)->(1,8,1)"
 
 # HBM bytes per launch of the copy kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE runs, or None.

@@ -222,8 +222,9 @@ const char* tpx_last_error(void);
 /* Global tuning knobs, read by later tpx_plan / tpx_execute calls on any thread:
  *   "tile_bytes"  upper bound of bytes per tile (power of two, 4096 .. 4194304; default 131072); small jobs
  *                 use smaller tiles, down to 16384, so that the launch still has thousands of workgroups
- *   "variant"     kernel variant, a bit field documented in the kernel source (default 91: 1024 threads per
- *                 workgroup, eight 16-byte loads in flight per thread, nontemporal loads and stores)
+ *   "variant"     kernel variant, 0 (default) = chosen from the tile size: 1024 threads per workgroup with eight
+ *                 nontemporal 16-byte loads in flight per thread for 128 KiB tiles, smaller workgroups for
+ *                 smaller tiles; other values are a bit field documented in the kernel source
  * Errors: INVALID_ARG for an unknown key or a value out of range. */
 tpx_status tpx_set_option(const char* key, uint64_t value);
 

@@ -166,6 +166,7 @@ tpx_status tpx_set_option(const char* key, uint64_t value) {
     return TPX_OK;
   }
   if (!std::strcmp(key, "variant")) {
+    if (value == 0) { tuning().variant = 0; return TPX_OK; }
     if (value > 95 || (value & 7) < 2 || (value & 7) > 4 || (((value >> 3) & 1) != ((value >> 4) & 1)))
       return fail(TPX_ERR_INVALID_ARG, "variant out of range");
     tuning().variant = value;

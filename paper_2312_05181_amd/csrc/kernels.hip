@@ -169,23 +169,58 @@ __device__ __forceinline__ void merge_tile(const tpx_tile& t, const tpx_segment*
 }
 
 // Transposing tile: element (i, j) is contiguous in j on the source and in i on the destination.
-// Sub-tiles of TI x TJ elements go through LDS so that both the global reads and the global writes
-// are coalesced.  lds holds TI x (TJ + 1) elements of type E.
-template <typename E, int kThreads, int TI, int TJ>
+// Square sub-tiles of TS x TS elements (at least 256 bytes a side) go through LDS: 16-byte global loads
+// along j, element-wise LDS writes into the transposed position, 16-byte reads along i, 16-byte global
+// stores.  Ragged or misaligned sub-tiles take the same route one element at a time.
+// lds holds TS x (TS + 1) elements of type E, addressed [j][i].
+template <typename E>
+struct TransposeShape {
+  static constexpr int VE = 16 / int(sizeof(E));                          // elements per 16-byte vector
+  static constexpr int TS = sizeof(E) == 1 ? 128 : 256 / int(sizeof(E));  // 128, 128, 64, 32
+  static constexpr int LD = TS + 1;
+  static constexpr int kBytes = TS * LD * int(sizeof(E));
+};
+
+template <typename E, int kThreads, bool NTL, bool NTS>
 __device__ __forceinline__ void transpose_tile(const uint8_t* __restrict__ s, uint8_t* __restrict__ d, uint32_t nJ,
                                                uint32_t nI, uint64_t sp, uint64_t dstep, void* lds_raw) {
-  E(*lds)[TJ + 1] = reinterpret_cast<E(*)[TJ + 1]>(lds_raw);
-  for (uint32_t i0 = 0; i0 < nI; i0 += TI)
-    for (uint32_t j0 = 0; j0 < nJ; j0 += TJ) {
-      const uint32_t ni = min(uint32_t(TI), nI - i0), nj = min(uint32_t(TJ), nJ - j0);
-      for (uint32_t e = threadIdx.x; e < TI * TJ; e += kThreads) {
-        const uint32_t i = e / TJ, j = e % TJ;
-        if (i < ni && j < nj) lds[i][j] = *reinterpret_cast<const E*>(s + uint64_t(i0 + i) * sp + uint64_t(j0 + j) * sizeof(E));
-      }
-      __syncthreads();
-      for (uint32_t e = threadIdx.x; e < TI * TJ; e += kThreads) {
-        const uint32_t j = e / TI, i = e % TI;
-        if (i < ni && j < nj) *reinterpret_cast<E*>(d + uint64_t(i0 + i) * sizeof(E) + uint64_t(j0 + j) * dstep) = lds[i][j];
+  using Sh = TransposeShape<E>;
+  constexpr int VE = Sh::VE, TS = Sh::TS, LD = Sh::LD;
+  E* lds = reinterpret_cast<E*>(lds_raw);
+  const bool aligned = reinterpret_cast<uintptr_t>(s) % 16 == 0 && sp % 16 == 0 &&
+                       reinterpret_cast<uintptr_t>(d) % 16 == 0 && dstep % 16 == 0;
+  for (uint32_t i0 = 0; i0 < nI; i0 += TS)
+    for (uint32_t j0 = 0; j0 < nJ; j0 += TS) {
+      const uint32_t ni = min(uint32_t(TS), nI - i0), nj = min(uint32_t(TS), nJ - j0);
+      if (aligned && ni == TS && nj == TS) {
+        for (uint32_t v = threadIdx.x; v < TS * TS / VE; v += kThreads) {
+          const uint32_t i = v / (TS / VE), jv = v % (TS / VE);
+          const v4u x = ld<v4u, NTL>(reinterpret_cast<const v4u*>(s + uint64_t(i0 + i) * sp + uint64_t(j0 + jv * VE) * sizeof(E)));
+          E e[VE];
+          __builtin_memcpy(e, &x, 16);
+#pragma unroll
+          for (int k = 0; k < VE; ++k) lds[(jv * VE + k) * LD + i] = e[k];
+        }
+        __syncthreads();
+        for (uint32_t v = threadIdx.x; v < TS * TS / VE; v += kThreads) {
+          const uint32_t j = v / (TS / VE), iv = v % (TS / VE);
+          E e[VE];
+#pragma unroll
+          for (int k = 0; k < VE; ++k) e[k] = lds[j * LD + iv * VE + k];
+          v4u x;
+          __builtin_memcpy(&x, e, 16);
+          st<v4u, NTS>(reinterpret_cast<v4u*>(d + uint64_t(j0 + j) * dstep + uint64_t(i0 + iv * VE) * sizeof(E)), x);
+        }
+      } else {
+        for (uint32_t e = threadIdx.x; e < TS * TS; e += kThreads) {
+          const uint32_t i = e / TS, jj = e % TS;
+          if (i < ni && jj < nj) lds[jj * LD + i] = *reinterpret_cast<const E*>(s + uint64_t(i0 + i) * sp + uint64_t(j0 + jj) * sizeof(E));
+        }
+        __syncthreads();
+        for (uint32_t e = threadIdx.x; e < TS * TS; e += kThreads) {
+          const uint32_t jj = e / TS, i = e % TS;
+          if (i < ni && jj < nj) *reinterpret_cast<E*>(d + uint64_t(i0 + i) * sizeof(E) + uint64_t(j0 + jj) * dstep) = lds[jj * LD + i];
+        }
       }
       __syncthreads();
     }
@@ -201,7 +236,9 @@ __device__ __forceinline__ void gather_tile(const uint8_t* __restrict__ s, uint8
   }
 }
 
-constexpr int kLdsBytes = 64 * 65 * 4;  // largest transposing sub-tile
+constexpr int kLdsBytes = TransposeShape<uint16_t>::kBytes;  // the largest transposing sub-tile (33,024 bytes)
+static_assert(kLdsBytes >= TransposeShape<uint8_t>::kBytes && kLdsBytes >= TransposeShape<uint32_t>::kBytes &&
+                  kLdsBytes >= TransposeShape<uint64_t>::kBytes, "LDS budget");
 
 template <int kThreads, int U, bool NTL, bool NTS>
 __global__ __launch_bounds__(kThreads) void tpx_execute_tiles(const tpx::FlatBox* __restrict__ boxes,
@@ -237,10 +274,10 @@ __global__ __launch_bounds__(kThreads) void tpx_execute_tiles(const tpx::FlatBox
     uint8_t* d = ds.base(c);
     if (t.kind == TPX_TILE_TRANSPOSE) {
       switch (t.unit_log2) {
-        case 3: transpose_tile<uint64_t, kThreads, 32, 64>(s, d, t.run_units, t.nrows, t.src_pitch, t.dst_step, lds_raw); break;
-        case 2: transpose_tile<uint32_t, kThreads, 64, 64>(s, d, t.run_units, t.nrows, t.src_pitch, t.dst_step, lds_raw); break;
-        case 1: transpose_tile<uint16_t, kThreads, 64, 64>(s, d, t.run_units, t.nrows, t.src_pitch, t.dst_step, lds_raw); break;
-        default: transpose_tile<uint8_t, kThreads, 64, 64>(s, d, t.run_units, t.nrows, t.src_pitch, t.dst_step, lds_raw); break;
+        case 3: transpose_tile<uint64_t, kThreads, NTL, NTS>(s, d, t.run_units, t.nrows, t.src_pitch, t.dst_step, lds_raw); break;
+        case 2: transpose_tile<uint32_t, kThreads, NTL, NTS>(s, d, t.run_units, t.nrows, t.src_pitch, t.dst_step, lds_raw); break;
+        case 1: transpose_tile<uint16_t, kThreads, NTL, NTS>(s, d, t.run_units, t.nrows, t.src_pitch, t.dst_step, lds_raw); break;
+        default: transpose_tile<uint8_t, kThreads, NTL, NTS>(s, d, t.run_units, t.nrows, t.src_pitch, t.dst_step, lds_raw); break;
       }
     } else {
       switch (t.unit_log2) {
@@ -352,6 +389,12 @@ tpx_status hip_launch_tiles(const void* workspace, const tpx_plan_s& plan, const
   }
   const WorkspaceLayout w = workspace_layout(plan);
   const uint8_t* base = static_cast<const uint8_t*>(workspace);
+  if (variant == 0) {
+    // automatic: a workgroup should load its whole tile at once (threads x loads in flight x 16 bytes = tile)
+    variant = plan.tile_bytes_used >= 131072 ? (3 | 24 | (2 << 5))   // 1024 threads x 8
+            : plan.tile_bytes_used >= 65536  ? (3 | 24 | (1 << 5))   //  512 threads x 8
+                                             : (2 | 24);             //  256 threads x 4 (small jobs, small tiles)
+  }
   KernelFn k = pick_kernel(variant);
   hipLaunchKernelGGL(k, dim3(uint32_t(plan.n_tiles)), dim3(threads_of(variant)), plan.needs_lds ? kLdsBytes : 0,
                      static_cast<hipStream_t>(stream), reinterpret_cast<const FlatBox*>(base + w.boxes_off),

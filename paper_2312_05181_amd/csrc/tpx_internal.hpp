@@ -55,7 +55,7 @@ tpx_status build_side(const tpx_model& m, const tpx_parallel& par, Side& out);
 
 struct Tuning {
   uint64_t tile_bytes = 131072;
-  uint64_t variant = 91;  // 1024 threads, 8 loads in flight per thread, nontemporal loads and stores
+  uint64_t variant = 0;   // 0 = chosen from the tile size (1024 threads x 8 nontemporal loads for 128 KiB tiles)
 };
 Tuning& tuning();
 

@@ -66,7 +66,7 @@ def test_every_kernel_variant(cuda, variant):
         _check_small(WIDE, synth.MIX_GPT, Parallel(4, 1, 1), Parallel(2, 2, 1))
         _check_small(ODD, ODD_MIX, Parallel(3, 1, 1), Parallel(4, 1, 1))
     finally:
-        tpx.tpx_set_option("variant", 91)
+        tpx.tpx_set_option("variant", 0)
         tpx.tpx_set_option("tile_bytes", 131072)
 
 
@@ -259,3 +259,21 @@ def test_multicast_small(cuda):
     _check_small(ODD, ODD_MIX, Parallel(3, 1, 1), Parallel(4, 1, 2))
     _check_small(SMALL, SMALL_MIX, Parallel(2, 1, 1), Parallel(3, 2, 2, w_transposed=1))
     _check_small(WIDE, synth.MIX_GPT, Parallel(2, 1, 2), Parallel(4, 1, 4))
+
+
+MID = Model(n_layers=2, hidden=512, n_heads=8, ffn=2048, vocab_true=4096, max_pos=64)
+
+
+@pytest.mark.parametrize("src,dst", [
+    (Parallel(2, 1, 1), Parallel(4, 1, 1, w_transposed=1)),
+    (Parallel(4, 1, 1, w_transposed=1, qkv_layout=1), Parallel(2, 2, 1)),
+    (Parallel(2, 1, 1, w_transposed=1), Parallel(2, 1, 2, qkv_layout=1)),
+    (Parallel(1, 1, 1), Parallel(8, 1, 1, w_transposed=1, qkv_layout=1)),
+])
+def test_transposed_storage_mid_size(cuda, src, dst):
+    """[in, out] weight storage on one side: full 128 x 128 (bf16) and 64 x 64 (fp32) sub-tiles take the
+    vectorised LDS path, edges the element path; compared byte for byte with the oracle."""
+    print("case", src, dst, flush=True)
+    plan = _check_small(MID, synth.MIX_GPT, src, dst, seed=23)
+    kinds = {b.kind for b in plan.boxes()}
+    assert 2 in kinds        # TPX_BOX_TRANSPOSE

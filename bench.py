@@ -83,6 +83,7 @@ def main() -> int:
     ap.add_argument("--cpu-layers", type=int, default=8, help="layers in the CPU oracle's sample (0 = skip)")
     ap.add_argument("--tile-bytes", type=int, default=0)
     ap.add_argument("--variant", type=int, default=-1)
+    ap.add_argument("--streams", type=int, default=0)
     ap.add_argument("--no-probe", action="store_true")
     ap.add_argument("--fill", choices=["synth", "cheap"], default="synth",
                     help="source contents: seeded synthetic state, or one cheap fill per buffer (for profiler runs)")
@@ -106,6 +107,8 @@ def main() -> int:
         tpx.tpx_set_option("tile_bytes", args.tile_bytes)
     if args.variant >= 0:
         tpx.tpx_set_option("variant", args.variant)
+    if args.streams:
+        tpx.tpx_set_option("streams", args.streams)
 
     model, src, dst, mixname, seed = WORKLOADS[args.workload]
     mix = synth.MIX_TINY if mixname == "tiny" else synth.MIX_GPT

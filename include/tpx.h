@@ -225,6 +225,9 @@ const char* tpx_last_error(void);
  *   "variant"     kernel variant, 0 (default) = chosen from the tile size: 1024 threads per workgroup with eight
  *                 nontemporal 16-byte loads in flight per thread for 128 KiB tiles, smaller workgroups for
  *                 smaller tiles; other values are a bit field documented in the kernel source
+ *   "streams"     tile order (1 .. 1024; default 4): workgroup b executes the (b / streams)-th tile of the
+ *                 (b % streams)-th contiguous part of the plan, so concurrent workgroups touch `streams`
+ *                 distant regions of the buffers
  * Errors: INVALID_ARG for an unknown key or a value out of range. */
 tpx_status tpx_set_option(const char* key, uint64_t value);
 

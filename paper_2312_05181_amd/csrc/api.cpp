@@ -172,6 +172,16 @@ tpx_status tpx_set_option(const char* key, uint64_t value) {
     tuning().variant = value;
     return TPX_OK;
   }
+  if (!std::strcmp(key, "max_multicast")) {
+    if (value < 1 || value > 128) return fail(TPX_ERR_INVALID_ARG, "max_multicast must be in [1, 128]");
+    tuning().max_multicast = value;
+    return TPX_OK;
+  }
+  if (!std::strcmp(key, "streams")) {
+    if (value < 1 || value > 1024) return fail(TPX_ERR_INVALID_ARG, "streams must be in [1, 1024]");
+    tuning().streams = value;
+    return TPX_OK;
+  }
   return fail(TPX_ERR_INVALID_ARG, std::string("unknown option ") + key);
 }
 

@@ -245,13 +245,22 @@ __global__ __launch_bounds__(kThreads) void tpx_execute_tiles(const tpx::FlatBox
                                                               const uint32_t* __restrict__ first_tile,
                                                               const uint32_t* __restrict__ coarse,
                                                               const tpx_segment* __restrict__ segs, uint32_t n_boxes,
-                                                              PtrTable ptrs) {
+                                                              uint32_t n_tiles, uint32_t streams, PtrTable ptrs) {
   extern __shared__ __align__(16) uint8_t lds_raw[];
   __shared__ SegLds lseg[kMaxSegLds];
   // locate this workgroup's tile: uniform for the whole workgroup, so these are scalar loads
-  const uint32_t box = tpx::find_box(first_tile, coarse, n_boxes, blockIdx.x);
+  // With `streams` = S > 1 the tile numbers are permuted so that workgroup b works on stream b % S, each
+  // stream being a contiguous 1/S of the tile sequence (gridDim.x is a multiple of S then).  The workgroups
+  // in flight at any moment then touch S distant regions of the rank buffers instead of one, which spreads
+  // the load over HBM channels and banks; all streams advance at the same rate, so they end together.
+  uint32_t tile_no = blockIdx.x;
+  if (streams > 1) {
+    tile_no = (blockIdx.x % streams) * (gridDim.x / streams) + (blockIdx.x / streams);
+    if (tile_no >= n_tiles) return;
+  }
+  const uint32_t box = tpx::find_box(first_tile, coarse, n_boxes, tile_no);
   const tpx::FlatBox fb = boxes[box];
-  const tpx_tile t = tpx::tile_of(fb, blockIdx.x - fb.first_tile);
+  const tpx_tile t = tpx::tile_of(fb, tile_no - fb.first_tile);
   const DstSet ds{ptrs.dst, t.dst_off, t.dst_rank, t.dst_rank_stride, t.n_dst};
   const bool mc = t.n_dst > 1;
   if (t.kind == TPX_TILE_FILL) {
@@ -309,7 +318,7 @@ tpx_status hip_fail(hipError_t e, const char* what) {
   return tpx::fail(TPX_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
 }
 
-using KernelFn = void (*)(const tpx::FlatBox*, const uint32_t*, const uint32_t*, const tpx_segment*, uint32_t, PtrTable);
+using KernelFn = void (*)(const tpx::FlatBox*, const uint32_t*, const uint32_t*, const tpx_segment*, uint32_t, uint32_t, uint32_t, PtrTable);
 
 template <int T, int U>
 KernelFn pick_nt(bool nt) {
@@ -395,12 +404,17 @@ tpx_status hip_launch_tiles(const void* workspace, const tpx_plan_s& plan, const
             : plan.tile_bytes_used >= 65536  ? (3 | 24 | (1 << 5))   //  512 threads x 8
                                              : (2 | 24);             //  256 threads x 4 (small jobs, small tiles)
   }
+  // interleaving several parts of the plan pays only when tiles cost the same; a plan that mixes plain and
+  // replicated moves runs in plan order
+  const uint32_t streams = plan.uniform_tiles ? uint32_t(std::max<uint64_t>(1, tuning().streams)) : 1;
+  const uint32_t grid = uint32_t((plan.n_tiles + streams - 1) / streams * streams);
   KernelFn k = pick_kernel(variant);
-  hipLaunchKernelGGL(k, dim3(uint32_t(plan.n_tiles)), dim3(threads_of(variant)), plan.needs_lds ? kLdsBytes : 0,
+  hipLaunchKernelGGL(k, dim3(grid), dim3(threads_of(variant)), plan.needs_lds ? kLdsBytes : 0,
                      static_cast<hipStream_t>(stream), reinterpret_cast<const FlatBox*>(base + w.boxes_off),
                      reinterpret_cast<const uint32_t*>(base + w.first_off),
                      reinterpret_cast<const uint32_t*>(base + w.coarse_off),
-                     reinterpret_cast<const tpx_segment*>(base + w.seg_off), uint32_t(plan.flat.size()), pt);
+                     reinterpret_cast<const tpx_segment*>(base + w.seg_off), uint32_t(plan.flat.size()),
+                     uint32_t(plan.n_tiles), streams, pt);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(e, "launching the tile kernel");
   return TPX_OK;

@@ -189,7 +189,7 @@ tpx_status plan_model_moves(tpx_plan_s& plan) {
       // pass 2: one set of moves per run of consecutive replicas with identical choices
       for (uint32_t d0 = 0; d0 < Dn;) {
         uint32_t d1 = d0 + 1;
-        while (d1 < Dn && choice[d1] == choice[d0]) ++d1;
+        while (d1 < Dn && d1 - d0 < tuning().max_multicast && choice[d1] == choice[d0]) ++d1;
         const uint32_t rn = r0 + d0 * Tn;
         size_t cursor = 0;
         for (const tpx_entry& sn : Sn.ranks[rn]) {
@@ -265,6 +265,8 @@ tpx_status tile_boxes(tpx_plan_s& plan, uint64_t tile_bytes) {
   while (tile_bytes > 16384 && total / tile_bytes < 8192) tile_bytes >>= 1;
   plan.tile_bytes_used = tile_bytes;
   plan.segments.clear();
+  plan.uniform_tiles = true;
+  for (const tpx_box& b : plan.boxes) plan.uniform_tiles = plan.uniform_tiles && b.n_dst == plan.boxes[0].n_dst;
   for (size_t bi = 0; bi < plan.boxes.size(); ++bi) {
     const tpx_box& b = plan.boxes[bi];
     if (box_bytes(b) == 0) continue;

@@ -55,6 +55,8 @@ tpx_status build_side(const tpx_model& m, const tpx_parallel& par, Side& out);
 
 struct Tuning {
   uint64_t tile_bytes = 131072;
+  uint64_t streams = 4;   // tile order: workgroup b works on contiguous part b % streams of the plan
+  uint64_t max_multicast = 8;  // most destinations one move may be replicated to
   uint64_t variant = 0;   // 0 = chosen from the tile size (1024 threads x 8 nontemporal loads for 128 KiB tiles)
 };
 Tuning& tuning();
@@ -74,6 +76,7 @@ struct tpx_plan_s {
   uint64_t tile_bytes_used = 0;
   tpx_stats_t stats{};
   bool needs_lds = false;       // some tile is staged through LDS
+  bool uniform_tiles = true;    // every tile has the same number of destinations (same cost per byte)
   void* uploaded_ws = nullptr;  // device workspace that currently holds the tables
 };
 

@@ -277,3 +277,19 @@ def test_transposed_storage_mid_size(cuda, src, dst):
     plan = _check_small(MID, synth.MIX_GPT, src, dst, seed=23)
     kinds = {b.kind for b in plan.boxes()}
     assert 2 in kinds        # TPX_BOX_TRANSPOSE
+
+
+@pytest.mark.parametrize("streams", [1, 3, 4, 7, 8, 64, 1000])
+def test_tile_order_streams(cuda, streams):
+    """Any tile order gives the same bytes, also when the tile count is not a multiple of the stream count
+    or smaller than it (the surplus workgroups exit)."""
+    print("streams", streams, flush=True)
+    tpx.tpx_set_option("streams", streams)
+    tpx.tpx_set_option("tile_bytes", 8192)
+    try:
+        plan = _check_small(WIDE, synth.MIX_GPT, Parallel(4, 1, 1), Parallel(2, 2, 1))
+        assert plan.num_tiles() % 7 != 0 or plan.num_tiles() % 64 != 0
+        _check_small(SMALL, SMALL_MIX, Parallel(2, 1, 1), Parallel(1, 1, 1))
+    finally:
+        tpx.tpx_set_option("streams", 4)
+        tpx.tpx_set_option("tile_bytes", 131072)

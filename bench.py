@@ -68,6 +68,8 @@ LAYOUT_PAIRS = {
     "gpt1.3b_(4,2,1)->(4,2,1)_transposed_dst": (_G13, _c(4, 2, 1), _c(4, 2, 1, w_transposed=1), "gpt", 23),
 }
 WORKLOADS.update(LAYOUT_PAIRS)
+DATASET_WORKLOAD = "dataset_1e8_D6->D4"
+DATASET_CFG = dict(n_samples=10 ** 8, global_batch=768, D_src=6, D_dst=4, steps_done=65000, seed=6)
 DEFAULT_WORKLOAD = "gpt6.7b_(8,1,1)->(1,8,1)"
 
 # HBM bytes per launch of the copy kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE runs, or None.
@@ -79,7 +81,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(WORKLOADS) + [DATASET_WORKLOAD])
     ap.add_argument("--cpu-layers", type=int, default=8, help="layers in the CPU oracle's sample (0 = skip)")
     ap.add_argument("--tile-bytes", type=int, default=0)
     ap.add_argument("--variant", type=int, default=-1)
@@ -109,6 +111,9 @@ def main() -> int:
         tpx.tpx_set_option("variant", args.variant)
     if args.streams:
         tpx.tpx_set_option("streams", args.streams)
+
+    if args.workload == DATASET_WORKLOAD:
+        return bench_dataset(args)
 
     model, src, dst, mixname, seed = WORKLOADS[args.workload]
     mix = synth.MIX_TINY if mixname == "tiny" else synth.MIX_GPT
@@ -222,6 +227,85 @@ def main() -> int:
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def bench_dataset(args) -> int:
+    """Dataset-state workload: 10^8 sample ids (uint64), global batch 768, 6 -> 4 replicas after 65,000 steps.
+    A step is tpx_plan_dataset + table upload + tpx_execute; the oracle repartitions the same arrays on the CPU."""
+    import numpy as np
+    import torch
+
+    import paper_2312_05181_amd as tpx
+    import synth
+
+    c = DATASET_CFG
+    n, B, D, D2 = c["n_samples"], c["global_batch"], c["D_src"], c["D_dst"]
+    b = B // D
+    full, tail = n // B, n % B
+    cursors = [min(full * b + max(0, min(b, tail - j * b)), c["steps_done"] * b) for j in range(D)]
+    plan = tpx.tpx_plan_dataset(n, B, D, D2, cursors)
+    stats = plan.stats()
+    G = synth.epoch_order(n, c["seed"])
+    # replica j holds, step by step, entries [k*B + j*b, k*B + (j+1)*b) of the global order
+    parts = []
+    for j in range(D):
+        body = G[:full * B].reshape(full, B)[:, j * b:(j + 1) * b].reshape(-1)
+        parts.append(np.concatenate([body, G[full * B + j * b: full * B + min(tail, (j + 1) * b)]]))
+    src_bufs = [torch.from_numpy(p.view(np.uint8)).cuda() for p in parts]
+    dst_bufs = [torch.zeros(plan.buffer_bytes(1, j), dtype=torch.uint8, device="cuda") for j in range(D2)]
+    ws = torch.empty(plan.workspace_bytes(), dtype=torch.uint8, device="cuda")
+    sp, dp = [x.data_ptr() for x in src_bufs], [x.data_ptr() for x in dst_bufs]
+    stream = torch.cuda.current_stream().cuda_stream
+    state_bytes = stats["bytes_read"] + stats["bytes_written"]
+
+    def step(e0=None, e1=None):
+        p = tpx.tpx_plan_dataset(n, B, D, D2, cursors)
+        p.prepare(ws.data_ptr(), stream)
+        if e0 is not None:
+            e0.record()
+        p.execute(sp, dp, ws.data_ptr(), stream)
+        if e1 is not None:
+            e1.record()
+        return p
+
+    for _ in range(args.warmup):
+        step()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    keep = [step(*e) for e in evs]
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    kernel_ms = [a.elapsed_time(b_) for a, b_ in evs]
+    kavg = sum(kernel_ms) / len(kernel_ms)
+    achieved = state_bytes / (kavg * 1e-3) / 1e9
+    del keep
+
+    cpu = None
+    if args.cpu_layers > 0:
+        from oracle import dataset as ods
+        t0 = time.perf_counter()
+        want, want_cur = ods.repartition(parts, cursors, B, D2)
+        secs = time.perf_counter() - t0
+        ok = plan.dst_cursors == want_cur and all(
+            np.array_equal(dst_bufs[j].cpu().numpy().view(np.uint64), want[j]) for j in range(D2))
+        cpu = {"value": round(state_bytes / secs / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "sample": "the whole workload (10^8 ids), numpy, single thread", "seconds": round(secs, 2),
+               "gpu_matches_oracle_on_sample": bool(ok)}
+    out = {"metric": "reshard_GBps_state_bytes_read_plus_written", "value": round(state_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+           "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+           "config": {"workload": args.workload, "state_bytes_read": stats["bytes_read"],
+                      "state_bytes_written": stats["bytes_written"], "n_boxes": stats["n_boxes"], "n_tiles": stats["n_tiles"],
+                      "src_ranks": D, "dst_ranks": D2},
+           "pct_of_hbm_peak": round(100 * achieved / HBM_PEAK_GBPS, 2),
+           "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                        "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None, "kernel": "tpx_execute_tiles",
+                        "kernel_ms_avg": round(kavg, 4), "kernel_ms_min": round(min(kernel_ms), 4),
+                        "algorithmic_bytes_per_launch": state_bytes},
+           "cpu_baseline": cpu}
     print(json.dumps(out), flush=True)
     return 0
 

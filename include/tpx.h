@@ -167,6 +167,30 @@ typedef struct {
  * INDIVISIBLE, BAD_STAGE_MAP, UNRECOVERABLE (src->rank_alive leaves a tensor without holder), OOM. */
 tpx_status tpx_plan(const tpx_model* model, const tpx_parallel* src, const tpx_parallel* dst, tpx_plan_t** out);
 
+/* A parallelizable tensor collection given explicitly (section 4.1, equation 1; section 5.1: the per-GPU
+ * description a model parallelizer hands over): for every rank, the sub-tensors it stores.  sigma is the
+ * set of boxes [lo, hi) of each tensor, phi and alpha are "which rank's list an entry is in" and its
+ * offset.  Anything expressible this way can be re-partitioned: tensor, pipeline and data parallelism,
+ * expert parallelism (phi groups whole expert tensors), sequence parallelism (sigma slices sample
+ * tensors), sharded optimizer state (section 4.3).  Used fields of tpx_entry: tensor_id and kind (together
+ * the identity of a state tensor), elem_bytes (1, 2, 4, 8), ndim (1..4), offset, full_shape, lo, hi, perm;
+ * nbytes may be 0 (computed); name and layer are not interpreted. */
+typedef struct {
+  uint32_t n_ranks;                 /* 1..TPX_MAX_RANKS */
+  const uint32_t* n_entries;        /* n_ranks counts */
+  const tpx_entry* const* entries;  /* n_ranks arrays */
+  const uint64_t* rank_bytes;       /* n_ranks buffer sizes, or NULL: end of the last sub-tensor rounded up to 256 */
+  const uint8_t* rank_alive;        /* n_ranks flags, 0 = lost (source only), or NULL */
+} tpx_ptc;
+
+/* Plan the transformation of PTC src into PTC dst over the same tensors (algorithm 1).  Within one side the
+ * sub-tensors of a tensor must be equal (replicas) or disjoint; the source's must tile every destination
+ * sub-tensor, except rows of axis 0 beyond the source tensor's extent, which are zero-filled.  Destination
+ * ranks with identical manifests whose indices form an arithmetic progression are treated as replicas
+ * (multicast moves).  Errors: INVALID_ARG (malformed entry, overlap, missing tensor, no tiling),
+ * UNRECOVERABLE, OOM. */
+tpx_status tpx_plan_ptc(const tpx_ptc* src, const tpx_ptc* dst, tpx_plan_t** out);
+
 /* Plan the transformation of the dataset state (sections 2.2 and 5.2): per-replica sample-index arrays
  * of one epoch are re-partitioned from D_src to D_dst replicas with the global batch unchanged, so that
  * the job consumes the same samples in the same order.  Replica j's index array holds, for every step k,

@@ -53,13 +53,17 @@ def holders(model: Model, par: Parallel, tid: int, kind: int):
 
 
 class Layout:
-    """All rank manifests of one configuration, indexed by (tensor id, kind)."""
+    """All rank manifests of one configuration, indexed by (tensor id, kind).
 
-    def __init__(self, model: Model, par: Parallel):
+    Built either from a (model, parallel configuration) pair or from explicit manifests: a list, per rank,
+    of (entries, buffer bytes) - the general form of a parallelizable tensor collection (paper section 4.1)."""
+
+    def __init__(self, model: Optional[Model] = None, par: Optional[Parallel] = None, manifests=None):
+        if manifests is None:
+            manifests = [spec.rank_manifest(model, par, rank) for rank in range(par.n_ranks)]
         self.sizes = []
         self.by_tensor = {}
-        for rank in range(par.n_ranks):
-            entries, nbytes = spec.rank_manifest(model, par, rank)
+        for rank, (entries, nbytes) in enumerate(manifests):
             self.sizes.append(nbytes)
             for e in entries:
                 self.by_tensor.setdefault((e.tensor_id, e.kind), []).append((rank, e))
@@ -148,6 +152,31 @@ def reshard(model: Model, src: Parallel, dst: Parallel, src_bufs: list,
         for rank, e, block in reshard_tensor(model, src, dst, src_lay, dst_lay, tk[0], tk[1], read):
             dst_bufs[rank][e.offset:e.offset + block.nbytes] = block.reshape(-1).view(np.uint8)
 
+    if threads > 1:
+        with ThreadPoolExecutor(threads) as ex:
+            list(ex.map(one, work))
+    else:
+        for tk in work:
+            one(tk)
+    return dst_bufs
+
+
+def reshard_ptc(src_manifests, dst_manifests, src_bufs: list, threads: int = 1) -> list:
+    """The same definition for collections given explicitly (expert, sequence, sharded-optimizer layouts ...):
+    manifests are lists, per rank, of (entries, buffer bytes)."""
+    src_lay, dst_lay = Layout(manifests=src_manifests), Layout(manifests=dst_manifests)
+    if len(src_bufs) != len(src_lay.sizes):
+        raise ValueError("need one source buffer per source rank")
+    dst_bufs = [np.full(n, spec.POISON, dtype=np.uint8) for n in dst_lay.sizes]
+
+    def read(rank, off, n):
+        return src_bufs[rank][off:off + n]
+
+    def one(tk):
+        for rank, e, block in reshard_tensor(None, None, None, src_lay, dst_lay, tk[0], tk[1], read):
+            dst_bufs[rank][e.offset:e.offset + block.nbytes] = block.reshape(-1).view(np.uint8)
+
+    work = sorted(dst_lay.by_tensor)
     if threads > 1:
         with ThreadPoolExecutor(threads) as ex:
             list(ex.map(one, work))

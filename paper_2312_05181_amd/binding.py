@@ -77,6 +77,12 @@ class tpx_segment(C.Structure):
     _fields_ = [("src_off", C.c_uint64), ("src_pitch", C.c_uint64), ("src_rank", C.c_uint32), ("pad_", C.c_uint32)]
 
 
+class tpx_ptc(C.Structure):
+    _fields_ = [("n_ranks", C.c_uint32), ("n_entries", C.POINTER(C.c_uint32)),
+                ("entries", C.POINTER(C.POINTER(tpx_entry))), ("rank_bytes", C.POINTER(C.c_uint64)),
+                ("rank_alive", C.POINTER(C.c_uint8))]
+
+
 class tpx_stats_t(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in ("n_pieces", "n_boxes", "n_tiles", "bytes_read", "bytes_written",
                                           "bytes_fill", "bytes_cross_rank", "plan_ns")]
@@ -87,6 +93,7 @@ assert C.sizeof(tpx_tile) == 80
 _P = C.c_void_p
 _sigs = {
     "tpx_plan": (C.c_int, [C.POINTER(tpx_model), C.POINTER(tpx_parallel), C.POINTER(tpx_parallel), C.POINTER(_P)]),
+    "tpx_plan_ptc": (C.c_int, [C.POINTER(tpx_ptc), C.POINTER(tpx_ptc), C.POINTER(_P)]),
     "tpx_plan_dataset": (C.c_int, [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32,
                                    C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(_P)]),
     "tpx_num_buffers": (C.c_uint32, [_P, C.c_int]),
@@ -233,6 +240,47 @@ def tpx_plan(model: dict, src: dict, dst: dict) -> Plan:
     d, keep_d = _parallel_struct(**dst)
     h = _P()
     _check(_lib.tpx_plan(C.byref(m), C.byref(s), C.byref(d), C.byref(h)))
+    del keep_s, keep_d
+    return Plan(h.value)
+
+
+def _ptc_struct(manifests, rank_bytes=None, rank_alive=None):
+    """manifests: per rank, a list of objects with attributes tensor_id, kind, elem_bytes, offset, full_shape,
+    lo, hi, perm (synth.ShardDesc has them; name and layer are optional)."""
+    keep = []
+    n = len(manifests)
+    counts = (C.c_uint32 * max(1, n))(*[len(m) for m in manifests])
+    ptrs = (C.POINTER(tpx_entry) * max(1, n))()
+    for r, man in enumerate(manifests):
+        arr = (tpx_entry * max(1, len(man)))()
+        for i, d in enumerate(man):
+            e = arr[i]
+            e.tensor_id, e.kind, e.elem_bytes, e.offset = d.tensor_id, d.kind, d.elem_bytes, d.offset
+            e.ndim = len(d.full_shape)
+            e.name, e.layer = getattr(d, "name", 0), getattr(d, "layer", -1)
+            for k in range(e.ndim):
+                e.full_shape[k], e.lo[k], e.hi[k], e.perm[k] = d.full_shape[k], d.lo[k], d.hi[k], d.perm[k]
+        keep.append(arr)
+        ptrs[r] = C.cast(arr, C.POINTER(tpx_entry))
+    c = tpx_ptc(n, C.cast(counts, C.POINTER(C.c_uint32)), C.cast(ptrs, C.POINTER(C.POINTER(tpx_entry))))
+    keep += [counts, ptrs]
+    if rank_bytes is not None:
+        rb = (C.c_uint64 * max(1, n))(*rank_bytes)
+        keep.append(rb)
+        c.rank_bytes = C.cast(rb, C.POINTER(C.c_uint64))
+    if rank_alive is not None:
+        ra = (C.c_uint8 * max(1, n))(*[1 if a else 0 for a in rank_alive])
+        keep.append(ra)
+        c.rank_alive = C.cast(ra, C.POINTER(C.c_uint8))
+    return c, keep
+
+
+def tpx_plan_ptc(src_manifests, dst_manifests, src_bytes=None, dst_bytes=None, src_alive=None) -> Plan:
+    """Plan between two explicitly given collections (any sharding expressible as boxes of tensors)."""
+    s, keep_s = _ptc_struct(src_manifests, src_bytes, src_alive)
+    d, keep_d = _ptc_struct(dst_manifests, dst_bytes)
+    h = _P()
+    _check(_lib.tpx_plan_ptc(C.byref(s), C.byref(d), C.byref(h)))
     del keep_s, keep_d
     return Plan(h.value)
 

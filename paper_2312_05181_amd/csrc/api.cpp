@@ -33,6 +33,7 @@ tpx_status tpx_plan(const tpx_model* model, const tpx_parallel* src, const tpx_p
     p->model = *model;
     tpx_status st = build_side(*model, *src, p->side[0]);
     if (!st) st = build_side(*model, *dst, p->side[1]);
+    if (!st) st = index_side(p->side[1], true);
     if (!st) st = plan_model_moves(*p);
     if (!st) st = finish_plan(*p);
     if (st) { delete p; return st; }
@@ -41,6 +42,48 @@ tpx_status tpx_plan(const tpx_model* model, const tpx_parallel* src, const tpx_p
     return TPX_OK;
   } catch (const std::bad_alloc&) {
     return fail(TPX_ERR_OOM, "tpx_plan: out of host memory");
+  }
+}
+
+static tpx_status side_from_ptc(const tpx_ptc* c, Side& out, const char* which) {
+  if (!c->n_ranks || c->n_ranks > TPX_MAX_RANKS) return fail(TPX_ERR_INVALID_ARG, std::string(which) + ": n_ranks must be 1..TPX_MAX_RANKS");
+  if (!c->n_entries || !c->entries) return fail(TPX_ERR_INVALID_ARG, std::string(which) + ": NULL entry tables");
+  out = Side{};
+  out.alive.assign(c->n_ranks, 1);
+  if (c->rank_alive) std::copy(c->rank_alive, c->rank_alive + c->n_ranks, out.alive.begin());
+  out.ranks.resize(c->n_ranks);
+  out.bytes.assign(c->n_ranks, 0);
+  for (uint32_t r = 0; r < c->n_ranks; ++r) {
+    if (c->n_entries[r] && !c->entries[r]) return fail(TPX_ERR_INVALID_ARG, std::string(which) + ": NULL entries for a rank");
+    out.ranks[r].assign(c->entries[r], c->entries[r] + c->n_entries[r]);
+    uint64_t end = 0;
+    for (const tpx_entry& e : out.ranks[r]) {
+      uint64_t numel = 1;
+      for (uint32_t k = 0; k < e.ndim && k < 4; ++k) numel *= e.hi[k] - e.lo[k];
+      end = std::max(end, e.offset + numel * e.elem_bytes);
+    }
+    out.bytes[r] = c->rank_bytes ? c->rank_bytes[r] : (end + kAlign - 1) / kAlign * kAlign;
+  }
+  return check_entries(out);
+}
+
+tpx_status tpx_plan_ptc(const tpx_ptc* src, const tpx_ptc* dst, tpx_plan_t** out) {
+  if (!src || !dst || !out) return fail(TPX_ERR_INVALID_ARG, "tpx_plan_ptc: NULL argument");
+  const uint64_t t0 = now_ns();
+  try {
+    tpx_plan_s* p = new tpx_plan_s();
+    tpx_status st = side_from_ptc(src, p->side[0], "source");
+    if (!st) st = side_from_ptc(dst, p->side[1], "destination");
+    if (!st) st = index_side(p->side[0], false);
+    if (!st) st = index_side(p->side[1], true);
+    if (!st) st = plan_model_moves(*p);
+    if (!st) st = finish_plan(*p);
+    if (st) { delete p; return st; }
+    p->stats.plan_ns = now_ns() - t0;
+    *out = p;
+    return TPX_OK;
+  } catch (const std::bad_alloc&) {
+    return fail(TPX_ERR_OOM, "tpx_plan_ptc: out of host memory");
   }
 }
 

@@ -37,7 +37,6 @@ tpx_status plan_dataset_moves(tpx_plan_s& plan, uint64_t n, uint32_t B, uint32_t
     s = Side{};
     const uint32_t deg = side ? Dn : D;
     const uint64_t w = side ? bn : b;
-    s.par.T = 1; s.par.P = 1; s.par.D = deg;
     s.alive.assign(deg, 1);
     s.ranks.resize(deg);
     s.bytes.resize(deg);

@@ -131,23 +131,21 @@ tpx_status build_side(const tpx_model& m, const tpx_parallel& par, Side& out) {
   if (m.n_heads % par.T || m.ffn % par.T || m.hidden % par.T)
     return fail(TPX_ERR_INDIVISIBLE, "heads, ffn or hidden not divisible by T");
   out = Side{};
-  out.par = par;
-  out.stage_first.resize(par.P + 1);
+  out.tp_degree = par.T;
+  std::vector<uint32_t> stage_first(par.P + 1);
   if (par.stage_first_layer) {
-    for (uint32_t p = 0; p <= par.P; ++p) out.stage_first[p] = par.stage_first_layer[p];
-    if (out.stage_first[0] != 0 || out.stage_first[par.P] != m.n_layers)
+    for (uint32_t p = 0; p <= par.P; ++p) stage_first[p] = par.stage_first_layer[p];
+    if (stage_first[0] != 0 || stage_first[par.P] != m.n_layers)
       return fail(TPX_ERR_BAD_STAGE_MAP, "stage boundaries must start at 0 and end at n_layers");
     for (uint32_t p = 0; p < par.P; ++p)
-      if (out.stage_first[p] > out.stage_first[p + 1])
+      if (stage_first[p] > stage_first[p + 1])
         return fail(TPX_ERR_BAD_STAGE_MAP, "stage boundaries must be ascending");
   } else {
     if (m.n_layers % par.P) return fail(TPX_ERR_INDIVISIBLE, "layers not divisible by P and no stage map given");
-    for (uint32_t p = 0; p <= par.P; ++p) out.stage_first[p] = p * (m.n_layers / par.P);
+    for (uint32_t p = 0; p <= par.P; ++p) stage_first[p] = p * (m.n_layers / par.P);
   }
-  out.par.stage_first_layer = nullptr;  // the copy above is authoritative; do not keep caller pointers
   out.alive.assign(n_ranks, 1);
   if (par.rank_alive) std::copy(par.rank_alive, par.rank_alive + n_ranks, out.alive.begin());
-  out.par.rank_alive = nullptr;
 
   Sigma sig[N_NAMES];
   for (uint32_t n = 0; n < N_NAMES; ++n)
@@ -155,13 +153,12 @@ tpx_status build_side(const tpx_model& m, const tpx_parallel& par, Side& out) {
 
   out.ranks.resize(n_ranks);
   out.bytes.assign(n_ranks, 0);
-  out.holders.assign(size_t(n_tensors_of(m)) * m.n_state_kinds, {});
 
   for (uint32_t p = 0; p < par.P; ++p) {
     // the tensors of stage p in packing order
     std::vector<std::pair<uint32_t, int32_t>> held;
     if (p == 0) { held.push_back({WORD_EMB, -1}); held.push_back({POS_EMB, -1}); }
-    for (uint32_t l = out.stage_first[p]; l < out.stage_first[p + 1]; ++l)
+    for (uint32_t l = stage_first[p]; l < stage_first[p + 1]; ++l)
       for (uint32_t n = LN1_W; n <= FC2_B; ++n) held.push_back({n, int32_t(l)});
     if (p == par.P - 1) {
       held.push_back({LNF_W, -1});
@@ -201,15 +198,119 @@ tpx_status build_side(const tpx_model& m, const tpx_parallel& par, Side& out) {
             e.offset = off;
             e.nbytes = numel * e.elem_bytes;
             off += e.nbytes;
-            out.holders[size_t(e.tensor_id) * m.n_state_kinds + k].push_back({rank, uint32_t(man.size())});
             man.push_back(e);
           }
         out.bytes[rank] = (off + kAlign - 1) / kAlign * kAlign;
       }
   }
-  // holders in ascending rank order, so "first alive holder" means lowest rank
-  for (auto& h : out.holders)
-    std::sort(h.begin(), h.end(), [](const Holder& x, const Holder& y) { return x.rank < y.rank; });
+  return index_side(out, false);
+}
+
+// Checks every entry of every manifest: shape, storage order, size, placement inside the rank buffer,
+// no two sub-tensors of a rank overlapping.  Fills nbytes.
+tpx_status check_entries(Side& side) {
+  for (size_t r = 0; r < side.ranks.size(); ++r) {
+    std::vector<std::pair<uint64_t, uint64_t>> spans;
+    for (tpx_entry& e : side.ranks[r]) {
+      const std::string where = "rank " + std::to_string(r) + " tensor " + std::to_string(e.tensor_id);
+      if (e.ndim < 1 || e.ndim > 4) return fail(TPX_ERR_INVALID_ARG, where + ": ndim must be 1..4");
+      if (e.elem_bytes != 1 && e.elem_bytes != 2 && e.elem_bytes != 4 && e.elem_bytes != 8)
+        return fail(TPX_ERR_INVALID_ARG, where + ": element size must be 1, 2, 4 or 8 bytes");
+      if (e.kind > 255) return fail(TPX_ERR_INVALID_ARG, where + ": state kind must be < 256");
+      uint32_t seen = 0;
+      uint64_t numel = 1;
+      for (uint32_t k = 0; k < e.ndim; ++k) {
+        if (e.perm[k] >= e.ndim || (seen >> e.perm[k]) & 1) return fail(TPX_ERR_INVALID_ARG, where + ": perm is not a permutation");
+        seen |= 1u << e.perm[k];
+        if (!(e.lo[k] < e.hi[k] && e.hi[k] <= e.full_shape[k])) return fail(TPX_ERR_INVALID_ARG, where + ": need lo < hi <= full_shape");
+        numel *= e.hi[k] - e.lo[k];
+      }
+      if (e.nbytes && e.nbytes != numel * e.elem_bytes) return fail(TPX_ERR_INVALID_ARG, where + ": nbytes does not match its box");
+      e.nbytes = numel * e.elem_bytes;
+      if (e.offset % e.elem_bytes) return fail(TPX_ERR_INVALID_ARG, where + ": offset is not a multiple of the element size");
+      if (e.offset + e.nbytes > side.bytes[r]) return fail(TPX_ERR_INVALID_ARG, where + ": extends past the end of its rank buffer");
+      spans.push_back({e.offset, e.offset + e.nbytes});
+    }
+    std::sort(spans.begin(), spans.end());
+    for (size_t i = 1; i < spans.size(); ++i)
+      if (spans[i].first < spans[i - 1].second) return fail(TPX_ERR_INVALID_ARG, "rank " + std::to_string(r) + ": two sub-tensors overlap in the buffer");
+  }
+  return TPX_OK;
+}
+
+// Builds the per-tensor index (which distinct boxes of a tensor exist, who holds each) and the replica
+// groups (ranks with identical manifests whose indices form an arithmetic progression).
+tpx_status index_side(Side& side, bool want_groups) {
+  side.key_of.clear();
+  side.subs.clear();
+  for (uint32_t r = 0; r < side.ranks.size(); ++r)
+    for (uint32_t i = 0; i < side.ranks[r].size(); ++i) {
+      const tpx_entry& e = side.ranks[r][i];
+      auto it = side.key_of.find(tensor_key(e));
+      if (it == side.key_of.end()) {
+        it = side.key_of.emplace(tensor_key(e), uint32_t(side.subs.size())).first;
+        side.subs.emplace_back();
+      }
+      auto& subs = side.subs[it->second];
+      if (!subs.empty()) {
+        const tpx_entry& f = side.ranks[subs[0].holders[0].rank][subs[0].holders[0].entry];
+        bool same = f.ndim == e.ndim && f.elem_bytes == e.elem_bytes;
+        for (uint32_t k = 0; same && k < e.ndim; ++k) same = f.full_shape[k] == e.full_shape[k];
+        if (!same) return fail(TPX_ERR_INVALID_ARG, "tensor " + std::to_string(e.tensor_id) + ": its sub-tensors disagree about shape or element size");
+      }
+      SubTensor* found = nullptr;
+      for (SubTensor& s : subs) {
+        bool equal = true, disjoint = false;
+        for (uint32_t k = 0; k < e.ndim; ++k) {
+          equal = equal && s.lo[k] == e.lo[k] && s.hi[k] == e.hi[k];
+          disjoint = disjoint || s.hi[k] <= e.lo[k] || e.hi[k] <= s.lo[k];
+        }
+        if (equal) { found = &s; break; }
+        if (!disjoint) return fail(TPX_ERR_INVALID_ARG, "tensor " + std::to_string(e.tensor_id) + ": sub-tensors overlap without being equal");
+      }
+      if (!found) {
+        subs.emplace_back();
+        found = &subs.back();
+        for (uint32_t k = 0; k < e.ndim; ++k) { found->lo[k] = e.lo[k]; found->hi[k] = e.hi[k]; }
+      }
+      found->holders.push_back({r, i});  // ranks are visited in ascending order
+    }
+  for (auto& subs : side.subs)
+    std::sort(subs.begin(), subs.end(), [](const SubTensor& a, const SubTensor& b) {
+      return std::lexicographical_compare(a.lo, a.lo + 4, b.lo, b.lo + 4);
+    });
+  // replica groups
+  side.groups.clear();
+  if (!want_groups) return TPX_OK;
+  std::vector<char> done(side.ranks.size(), 0);
+  auto same_manifest = [&](uint32_t a, uint32_t b) {
+    if (side.bytes[a] != side.bytes[b] || side.ranks[a].size() != side.ranks[b].size()) return false;
+    for (size_t i = 0; i < side.ranks[a].size(); ++i) {
+      const tpx_entry &x = side.ranks[a][i], &y = side.ranks[b][i];
+      if (x.tensor_id != y.tensor_id || x.kind != y.kind || x.offset != y.offset || x.elem_bytes != y.elem_bytes || x.ndim != y.ndim) return false;
+      for (uint32_t k = 0; k < x.ndim; ++k)
+        if (x.lo[k] != y.lo[k] || x.hi[k] != y.hi[k] || x.perm[k] != y.perm[k] || x.full_shape[k] != y.full_shape[k]) return false;
+    }
+    return true;
+  };
+  for (uint32_t r = 0; r < side.ranks.size(); ++r) {
+    if (done[r]) continue;
+    ReplicaGroup g{r, 1, 0};
+    done[r] = 1;
+    if (!side.ranks[r].empty())
+      for (uint32_t q = r + 1; q < side.ranks.size(); ++q) {
+        if (done[q] || !same_manifest(r, q)) continue;
+        const uint32_t stride = q - r;
+        if (stride > 255) break;
+        g.stride = stride;
+        for (uint32_t x = q; x < side.ranks.size() && g.count < 255 && !done[x] && same_manifest(r, x); x += stride) {
+          done[x] = 1;
+          ++g.count;
+        }
+        break;
+      }
+    side.groups.push_back(g);
+  }
   return TPX_OK;
 }
 

@@ -97,16 +97,14 @@ uint64_t box_bytes(const tpx_box& b) {
 // crosses), then (2) one with the destination's tensor-parallel index (only replicated tensors have a
 // choice here; it keeps a rank's neighbouring tensors coming from one source buffer, so their moves
 // merge), then (3) the lowest rank index.  Returns -1 if no holder survives.
-static int get_resource(const Side& src, const Side& dst, const std::vector<Holder>& hs, const uint64_t lo[4],
-                        const uint64_t hi[4], uint32_t ndim, uint32_t dst_rank) {
+static int get_resource(const Side& src, const Side& dst, const SubTensor& sub, uint32_t dst_rank) {
   int best = -1, best_score = 3;
-  const uint32_t t_dst = dst_rank % dst.par.T;
-  for (size_t i = 0; i < hs.size(); ++i) {
-    const tpx_entry& e = src.ranks[hs[i].rank][hs[i].entry];
-    bool contains = true;
-    for (uint32_t k = 0; k < ndim; ++k) contains = contains && e.lo[k] <= lo[k] && hi[k] <= e.hi[k];
-    if (!contains || !src.alive[hs[i].rank]) continue;
-    const int score = hs[i].rank == dst_rank ? 0 : (hs[i].rank % src.par.T == t_dst ? 1 : 2);
+  const bool tp = src.tp_degree && dst.tp_degree;
+  const uint32_t t_dst = tp ? dst_rank % dst.tp_degree : 0;
+  for (size_t i = 0; i < sub.holders.size(); ++i) {
+    const uint32_t r = sub.holders[i].rank;
+    if (!src.alive[r]) continue;
+    const int score = r == dst_rank ? 0 : (tp && r % src.tp_degree == t_dst ? 1 : 2);
     if (score < best_score) { best = int(i); best_score = score; }
   }
   return best;
@@ -114,38 +112,38 @@ static int get_resource(const Side& src, const Side& dst, const std::vector<Hold
 
 namespace {
 
-// SPLIT: W = get_split_tensors(t, sigma, sigma') for the new sub-tensor sn.  Walks sn's range on the sliced
-// axis; the next cut point is the nearer of the old sub-tensor's end and the new one's end.  Calls
-// fn(lo, hi, is_fill) per piece; is_fill marks rows that exist only as new padding.
+// SPLIT: W = get_split_tensors(t, sigma, sigma') for the new sub-tensor sn: its intersections with the
+// old sub-tensors of the same tensor, in position order.  Calls fn(lo, hi, sub) per piece; sub == nullptr
+// marks rows that exist only as new padding (axis 0 of the new tensor is longer than the old one's).
+// The old sub-tensors must tile the part of sn that exists in the old tensor.
 template <typename Fn>
-tpx_status for_each_piece(const tpx_entry& sn, const tpx_entry& any, Fn&& fn) {
-  // sliced axis: the one on which an old or new sub-tensor is narrower than the full tensor.
-  // Only the (padded) extent of axis 0 may differ between the two configurations.
-  int axis = -1;
+tpx_status for_each_piece(const tpx_entry& sn, const tpx_entry& any, const std::vector<SubTensor>& subs, Fn&& fn) {
+  if (any.ndim != sn.ndim || any.elem_bytes != sn.elem_bytes) return fail(TPX_ERR_INVALID_ARG, "tensor rank or element size differs between configurations");
+  for (uint32_t k = 1; k < sn.ndim; ++k)  // only the (padded) extent of axis 0 may differ
+    if (any.full_shape[k] != sn.full_shape[k]) return fail(TPX_ERR_INVALID_ARG, "tensor shapes differ between configurations");
+  const uint64_t old_rows = any.full_shape[0];
+  uint64_t want = 1, got = 0;
   for (uint32_t k = 0; k < sn.ndim; ++k) {
-    if (k > 0 && any.full_shape[k] != sn.full_shape[k]) return fail(TPX_ERR_INVALID_ARG, "tensor shapes differ between configurations");
-    if (sn.hi[k] - sn.lo[k] != sn.full_shape[k] || any.hi[k] - any.lo[k] != any.full_shape[k]) axis = int(k);
+    const uint64_t hi = k == 0 ? std::min(sn.hi[0], old_rows) : sn.hi[k];
+    want *= hi > sn.lo[k] ? hi - sn.lo[k] : 0;
   }
-  if (axis < 0 && any.full_shape[0] != sn.full_shape[0]) axis = 0;
-  uint64_t lo[4], hi[4];
-  for (uint32_t k = 0; k < 4; ++k) { lo[k] = sn.lo[k]; hi[k] = sn.hi[k]; }
-  if (axis < 0) return fn(lo, hi, false);  // unsliced on both sides: a single piece
-  const uint64_t old_part = any.hi[axis] - any.lo[axis];  // equal parts under sigma
-  const uint64_t old_full = any.full_shape[axis];
-  uint64_t pos = sn.lo[axis];
-  const uint64_t end = sn.hi[axis];
-  while (pos < end && pos < old_full) {
-    const uint64_t old_end = (pos / old_part + 1) * old_part;
-    const uint64_t cut = std::min(std::min(old_end, end), old_full);
-    lo[axis] = pos;
-    hi[axis] = cut;
-    if (tpx_status st = fn(lo, hi, false)) return st;
-    pos = cut;
+  for (const SubTensor& sub : subs) {
+    uint64_t lo[4] = {0, 0, 0, 0}, hi[4] = {0, 0, 0, 0}, vol = 1;
+    for (uint32_t k = 0; k < sn.ndim; ++k) {
+      lo[k] = std::max(sn.lo[k], sub.lo[k]);
+      hi[k] = std::min(sn.hi[k], sub.hi[k]);
+      vol *= hi[k] > lo[k] ? hi[k] - lo[k] : 0;
+    }
+    if (!vol) continue;
+    got += vol;
+    if (tpx_status st = fn(lo, hi, &sub)) return st;
   }
-  if (pos < end) {
-    lo[axis] = pos;
-    hi[axis] = end;
-    if (tpx_status st = fn(lo, hi, true)) return st;
+  if (got != want) return fail(TPX_ERR_INVALID_ARG, "the old sub-tensors of tensor " + std::to_string(sn.tensor_id) + " do not tile it");
+  if (sn.hi[0] > old_rows) {
+    uint64_t lo[4], hi[4];
+    for (uint32_t k = 0; k < 4; ++k) { lo[k] = sn.lo[k]; hi[k] = sn.hi[k]; }
+    lo[0] = std::max(sn.lo[0], old_rows);
+    if (tpx_status st = fn(lo, hi, nullptr)) return st;
   }
   return TPX_OK;
 }
@@ -155,61 +153,64 @@ tpx_status for_each_piece(const tpx_entry& sn, const tpx_entry& any, Fn&& fn) {
 tpx_status plan_model_moves(tpx_plan_s& plan) {
   const Side& S = plan.side[0];
   const Side& Sn = plan.side[1];
-  const uint32_t nk = plan.model.n_state_kinds;
-  const uint32_t Tn = Sn.par.T, Dn = Sn.par.D, Pn = Sn.par.P;
   plan.boxes.clear();
   uint64_t n_pieces = 0;
-  // RE-PARTITION: foreach r' in R', foreach sub-tensor s' allocated to r'.  The D' replicas of one (t', p')
-  // hold identical sub-collections at identical offsets; replicas that also make the same source choices
-  // are served by one multicast move (read once, written to each), so they are planned together.
-  for (uint32_t pn = 0; pn < Pn; ++pn)
-    for (uint32_t tn = 0; tn < Tn; ++tn) {
-      const uint32_t r0 = tn + Tn * Dn * pn;  // replica d' = 0; replica d' is r0 + d' * T'
-      // pass 1: every replica's source choice for every piece (get_resource)
-      std::vector<std::vector<int>> choice(Dn);
-      for (uint32_t dn = 0; dn < Dn; ++dn) {
-        const uint32_t rn = r0 + dn * Tn;
-        for (const tpx_entry& sn : Sn.ranks[r0]) {
-          const auto& hs = S.holders[size_t(sn.tensor_id) * nk + sn.kind];  // get_base_tensor: same tensor, old side
-          if (hs.empty()) return fail(TPX_ERR_INVALID_ARG, "tensor missing from the source configuration");
-          const tpx_entry& any = S.ranks[hs[0].rank][hs[0].entry];
-          tpx_status st = for_each_piece(sn, any, [&](const uint64_t* lo, const uint64_t* hi, bool is_fill) -> tpx_status {
-            if (is_fill) { choice[dn].push_back(-1); return TPX_OK; }
-            const int h = get_resource(S, Sn, hs, lo, hi, sn.ndim, rn);
-            if (h < 0)
-              return fail(TPX_ERR_UNRECOVERABLE, std::string("no surviving holder of a piece of ") + param_name(sn.name) +
-                                                     " layer " + std::to_string(sn.layer));
-            choice[dn].push_back(h);
-            ++n_pieces;
-            return TPX_OK;
-          });
-          if (st) return st;
-        }
-      }
-      // pass 2: one set of moves per run of consecutive replicas with identical choices
-      for (uint32_t d0 = 0; d0 < Dn;) {
-        uint32_t d1 = d0 + 1;
-        while (d1 < Dn && d1 - d0 < tuning().max_multicast && choice[d1] == choice[d0]) ++d1;
-        const uint32_t rn = r0 + d0 * Tn;
-        size_t cursor = 0;
-        for (const tpx_entry& sn : Sn.ranks[rn]) {
-          const auto& hs = S.holders[size_t(sn.tensor_id) * nk + sn.kind];
-          const tpx_entry& any = S.ranks[hs[0].rank][hs[0].entry];
-          tpx_status st = for_each_piece(sn, any, [&](const uint64_t* lo, const uint64_t* hi, bool is_fill) -> tpx_status {
-            const int h = choice[d0][cursor++];
-            tpx_box b = is_fill ? lower_piece(lo, hi, nullptr, 0, sn, rn)
-                                : lower_piece(lo, hi, &S.ranks[hs[h].rank][hs[h].entry], hs[h].rank, sn, rn);  // move(w, r_w, r')
-            b.n_dst = d1 - d0;
-            b.dst_rank_stride = Tn;
-            plan.boxes.push_back(b);
-            return TPX_OK;
-          });
-          if (st) return st;
-          // merge(W): implicit - the pieces were addressed inside s' itself
-        }
-        d0 = d1;
+  // RE-PARTITION: foreach r' in R', foreach sub-tensor s' allocated to r'.  Ranks of a replica group hold
+  // identical sub-collections at identical offsets; members that also make the same source choices are
+  // served by one multicast move (read once, written to each), so a group is planned together.
+  for (const ReplicaGroup& g : Sn.groups) {
+    const uint32_t r0 = g.first;
+    // pass 1: every member's source choice for every piece (get_resource)
+    std::vector<std::vector<int>> choice(g.count);
+    for (uint32_t dn = 0; dn < g.count; ++dn) {
+      const uint32_t rn = r0 + dn * g.stride;
+      for (const tpx_entry& sn : Sn.ranks[r0]) {
+        const auto key = S.key_of.find(tensor_key(sn));  // get_base_tensor: the same tensor, old side
+        if (key == S.key_of.end()) return fail(TPX_ERR_INVALID_ARG, "tensor " + std::to_string(sn.tensor_id) + " is missing from the source configuration");
+        const auto& subs = S.subs[key->second];
+        const tpx_entry& any = S.ranks[subs[0].holders[0].rank][subs[0].holders[0].entry];
+        tpx_status st = for_each_piece(sn, any, subs, [&](const uint64_t*, const uint64_t*, const SubTensor* sub) -> tpx_status {
+          if (!sub) { choice[dn].push_back(-1); return TPX_OK; }
+          const int h = get_resource(S, Sn, *sub, rn);
+          if (h < 0)
+            return fail(TPX_ERR_UNRECOVERABLE, "no surviving holder of a piece of tensor " + std::to_string(sn.tensor_id) +
+                                                   (sn.name < N_NAMES && S.tp_degree ? std::string(" (") + param_name(sn.name) + ", layer " + std::to_string(sn.layer) + ")" : std::string()));
+          choice[dn].push_back(h);
+          ++n_pieces;
+          return TPX_OK;
+        });
+        if (st) return st;
       }
     }
+    // pass 2: one set of moves per run of consecutive members with identical choices
+    for (uint32_t d0 = 0; d0 < g.count;) {
+      uint32_t d1 = d0 + 1;
+      while (d1 < g.count && d1 - d0 < tuning().max_multicast && choice[d1] == choice[d0]) ++d1;
+      const uint32_t rn = r0 + d0 * g.stride;
+      size_t cursor = 0;
+      for (const tpx_entry& sn : Sn.ranks[rn]) {
+        const auto& subs = S.subs[S.key_of.find(tensor_key(sn))->second];
+        const tpx_entry& any = S.ranks[subs[0].holders[0].rank][subs[0].holders[0].entry];
+        tpx_status st = for_each_piece(sn, any, subs, [&](const uint64_t* lo, const uint64_t* hi, const SubTensor* sub) -> tpx_status {
+          const int h = choice[d0][cursor++];
+          tpx_box b;
+          if (!sub) {
+            b = lower_piece(lo, hi, nullptr, 0, sn, rn);
+          } else {
+            const Holder& who = sub->holders[size_t(h)];
+            b = lower_piece(lo, hi, &S.ranks[who.rank][who.entry], who.rank, sn, rn);  // move(w, r_w, r')
+          }
+          b.n_dst = d1 - d0;
+          b.dst_rank_stride = b.n_dst > 1 ? g.stride : 0;
+          plan.boxes.push_back(b);
+          return TPX_OK;
+        });
+        if (st) return st;
+        // merge(W): implicit - the pieces were addressed inside s' itself
+      }
+      d0 = d1;
+    }
+  }
   plan.stats.n_pieces = n_pieces;
   return TPX_OK;
 }

@@ -3,6 +3,7 @@
 
 #include <cstdint>
 #include <string>
+#include <unordered_map>
 #include <vector>
 
 #include "tile_math.hpp"
@@ -32,15 +33,34 @@ struct Holder {
   uint32_t entry;  // index into Side::ranks[rank]
 };
 
-// One configuration applied to the model: phi and alpha evaluated for every rank.
+// One distinct sub-tensor of a state tensor (a box of the full tensor) and every rank that stores it
+// (data-parallel replicas, replicated tensors, tied copies), in ascending rank order.
+struct SubTensor {
+  uint64_t lo[4] = {0, 0, 0, 0}, hi[4] = {0, 0, 0, 0};
+  std::vector<Holder> holders;
+};
+
+// Ranks of the new configuration that hold identical sub-collections at identical offsets
+// (data-parallel replicas): first, first + stride, ...
+struct ReplicaGroup {
+  uint32_t first, count, stride;
+};
+
+// One PTC evaluated for every rank: sigma (the boxes), phi and alpha (which rank buffer, where).
 struct Side {
-  tpx_parallel par{};
-  std::vector<uint32_t> stage_first;          // P+1 boundaries
+  uint32_t tp_degree = 0;                     // T of a (T, P, D) configuration, 0 for an explicit PTC
   std::vector<uint8_t> alive;                 // per rank
   std::vector<std::vector<tpx_entry>> ranks;  // manifest of every rank buffer
   std::vector<uint64_t> bytes;                // size of every rank buffer
-  std::vector<std::vector<Holder>> holders;   // [tensor_id * n_kinds + kind] -> who stores a piece of it
+  // index, built by index_side(): state tensor (tensor_id, kind) -> dense key -> its distinct sub-tensors,
+  // sorted by position
+  std::unordered_map<uint64_t, uint32_t> key_of;
+  std::vector<std::vector<SubTensor>> subs;
+  std::vector<ReplicaGroup> groups;           // partition of the ranks into replica groups
 };
+inline uint64_t tensor_key(const tpx_entry& e) { return (uint64_t(e.tensor_id) << 8) | e.kind; }
+tpx_status check_entries(Side& side);  // validates every manifest entry, fills nbytes
+tpx_status index_side(Side& side, bool want_groups);  // builds key_of, subs (and groups) from ranks
 
 // Error reporting: sets the thread-local message and returns `st`.
 tpx_status fail(tpx_status st, const std::string& msg);

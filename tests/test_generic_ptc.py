@@ -1,0 +1,267 @@
+"""Collections given explicitly (paper section 4.3: the same three functions express expert parallelism,
+sequence parallelism and other strategies): the generic oracle against the value function, and libtpx's
+planner (interpreted on the CPU) against the generic oracle."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2312_05181_amd as tpx
+import paper_2312_05181_amd.binding as B
+import synth
+from oracle import reshard as oreshard
+from oracle import spec
+from tests import helpers as H
+from tests import host_exec
+
+MIX = ((2, "bf16w"), (4, "n02"), (4, "m"), (4, "v"))
+
+
+def pack(boxes):
+    """boxes: per rank a list of (tensor_id, kind, elem_bytes, full_shape, lo, hi, perm); assigns 256-aligned
+    offsets in list order.  Returns per rank (entries, nbytes)."""
+    out = []
+    for per_rank in boxes:
+        off, entries = 0, []
+        for tid, kind, eb, full, lo, hi, perm in per_rank:
+            off = -(-off // 256) * 256
+            entries.append(spec.Entry(tid, kind, eb, off, tuple(full), tuple(lo), tuple(hi), tuple(perm), 0, -1))
+            off += int(np.prod([h - l for l, h in zip(lo, hi)])) * eb
+        out.append((entries, -(-off // 256) * 256))
+    return out
+
+
+def even(n, parts, i):
+    return (n * i) // parts, (n * (i + 1)) // parts
+
+
+# ---- the collections ---------------------------------------------------------------------------------
+def experts(n_ranks, tp=1, n_experts=8, h=32, f=64):
+    """Expert parallelism: phi groups whole expert tensors (sigma is the identity); optionally each expert's
+    matrices are also tensor-parallel (tp) on the ffn axis.  Rank = ep_rank * tp + t."""
+    ranks = []
+    ep = n_ranks // tp
+    for r in range(n_ranks):
+        e_lo, e_hi = even(n_experts, ep, r // tp)
+        t = r % tp
+        per = []
+        for kind, eb in enumerate((2, 4, 4, 4)):
+            for e in range(e_lo, e_hi):
+                a, b = even(f, tp, t)
+                per.append((2 * e, kind, eb, (f, h), (a, 0), (b, h), (0, 1)))          # up-projection, rows cut
+                per.append((2 * e + 1, kind, eb, (h, f), (0, a), (h, b), (0, 1)))      # down-projection, columns cut
+        ranks.append(per)
+    return pack(ranks)
+
+
+def sequence(n_ranks, batch=4, seq=64, hidden=48):
+    """Sequence parallelism: sigma slices a sample tensor [batch, seq, hidden] along seq."""
+    ranks = []
+    for r in range(n_ranks):
+        a, b = even(seq, n_ranks, r)
+        ranks.append([(0, 0, 2, (batch, seq, hidden), (0, a, 0), (batch, b, hidden), (0, 1, 2))])
+    return pack(ranks)
+
+
+def sharded_optimizer(n_ranks, n=100_003):
+    """Optimizer state flattened and cut into contiguous chunks, one per data-parallel rank (uneven sizes)."""
+    ranks = []
+    for r in range(n_ranks):
+        a, b = even(n, n_ranks, r)
+        ranks.append([(0, k, 4, (n,), (a,), (b,), (0,)) for k in (1, 2, 3)])
+    return pack(ranks)
+
+
+def grid2d(rows, cols, shape=(64, 96)):
+    """Two-dimensional tensor parallelism: a rows x cols grid of blocks; rank = i * cols + j."""
+    ranks = []
+    for i in range(rows):
+        for j in range(cols):
+            a, b = even(shape[0], rows, i)
+            c, d = even(shape[1], cols, j)
+            ranks.append([(0, k, eb, shape, (a, c), (b, d), (0, 1)) for k, eb in enumerate((2, 4))])
+    return pack(ranks)
+
+
+def replicated(n_copies, base):
+    return [base[i % len(base)] for i in range(n_copies * len(base))]
+
+
+CASES = {
+    "experts 2 -> 4 ranks": (experts(2), experts(4)),
+    "experts 4 -> 2 ranks": (experts(4), experts(2)),
+    "experts ep2 -> ep2 x tp2": (experts(2), experts(4, tp=2)),
+    "experts ep4 x tp2 -> ep2": (experts(8, tp=2), experts(2)),
+    "sequence 2 -> 4": (sequence(2), sequence(4)),
+    "sequence 4 -> 1": (sequence(4), sequence(1)),
+    "sequence 3 -> 2 (uneven pieces)": (sequence(3, seq=66), sequence(2, seq=66)),
+    "sharded optimizer 3 -> 4": (sharded_optimizer(3), sharded_optimizer(4)),
+    "sharded optimizer 4 -> 1": (sharded_optimizer(4), sharded_optimizer(1)),
+    "2-D grid 2x2 -> 1x4": (grid2d(2, 2), grid2d(1, 4)),
+    "2-D grid 2x2 -> 4x1": (grid2d(2, 2), grid2d(4, 1)),
+    "2-D grid 1x4 -> 2x3": (grid2d(1, 4), grid2d(2, 3)),
+    "experts 2 -> 2 replicas of 2": (experts(2), replicated(2, experts(2))),
+}
+
+
+def src_buffers(man, seed, device="cpu"):
+    bufs = []
+    for entries, n in man:
+        b = torch.full((n,), H.SRC_GAP, dtype=torch.uint8, device=device)
+        synth.fill_buffer(b, [H.desc_of(e) for e in entries], seed, MIX)
+        bufs.append(b)
+    return bufs
+
+
+def closed_form(man, seed, device="cpu"):
+    bufs = []
+    for entries, n in man:
+        b = torch.full((n,), H.POISON, dtype=torch.uint8, device=device)
+        synth.fill_buffer(b, [H.desc_of(e) for e in entries], seed, MIX)
+        bufs.append(b)
+    return bufs
+
+
+def plan_of(src, dst, **kw):
+    return tpx.tpx_plan_ptc([[H.desc_of(e) for e in ent] for ent, _ in src], [[H.desc_of(e) for e in ent] for ent, _ in dst],
+                            src_bytes=[n for _, n in src], dst_bytes=[n for _, n in dst], **kw)
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_generic_oracle_matches_value_function_and_round_trips(name):
+    src, dst = CASES[name]
+    a = H.np_bufs(src_buffers(src, 5))
+    out = oreshard.reshard_ptc(src, dst, a)
+    want = H.np_bufs(closed_form(dst, 5))
+    assert all(np.array_equal(x, y) for x, y in zip(out, want))
+    back = oreshard.reshard_ptc(dst, src, out)
+    for r, (entries, _) in enumerate(src):
+        for e in entries:
+            d = H.desc_of(e)
+            assert np.array_equal(back[r][d.offset:d.offset + d.nbytes], a[r][d.offset:d.offset + d.nbytes])
+
+
+@pytest.mark.parametrize("how", ["boxes", "tiles"])
+@pytest.mark.parametrize("name", list(CASES))
+def test_generic_plan_matches_oracle(name, how):
+    src, dst = CASES[name]
+    a = H.np_bufs(src_buffers(src, 7))
+    want = oreshard.reshard_ptc(src, dst, a)
+    tpx.tpx_set_option("tile_bytes", 4096)
+    try:
+        plan = plan_of(src, dst)
+    finally:
+        tpx.tpx_set_option("tile_bytes", 131072)
+    got = [np.full(n, H.POISON, dtype=np.uint8) for _, n in dst]
+    cover = [np.zeros(n, dtype=np.int32) for _, n in dst]
+    (host_exec.run_boxes if how == "boxes" else host_exec.run_tiles)(plan, a, got, cover)
+    for r, (entries, n) in enumerate(dst):
+        assert plan.buffer_bytes(1, r) == n
+        assert np.array_equal(got[r], want[r]), r
+        expect = np.zeros(n, dtype=np.int32)
+        for e in entries:
+            d = H.desc_of(e)
+            expect[d.offset:d.offset + d.nbytes] = 1
+        assert np.array_equal(cover[r], expect)
+
+
+def test_expert_regrouping_moves_whole_tensors():
+    """Expert parallelism changes only phi: no sub-tensor is split, and neighbours merge into long runs."""
+    plan = plan_of(*CASES["experts 2 -> 4 ranks"])
+    assert all(b.kind == B.BOX_COPY and b.ndim == 0 for b in plan.boxes())
+    assert plan.stats()["n_boxes"] == 4 * 4          # one run per destination rank and state kind
+
+
+def test_identical_destination_ranks_are_replicas():
+    plan = plan_of(*CASES["experts 2 -> 2 replicas of 2"])
+    s = plan.stats()
+    assert s["bytes_written"] == 2 * s["bytes_read"]
+    assert all(b.n_dst == 2 and b.dst_rank_stride == 2 for b in plan.boxes())
+
+
+def test_generic_errors():
+    def st(fn):
+        with pytest.raises(tpx.TpxError) as ei:
+            fn()
+        return ei.value.status
+    src, dst = CASES["sequence 2 -> 4"]
+    # a destination tensor the source does not have
+    other = pack([[(9, 0, 2, (4, 64, 48), (0, 0, 0), (4, 64, 48), (0, 1, 2))]])
+    assert st(lambda: plan_of(src, other)) == B.TPX_ERR_INVALID_ARG
+    # the source covers only half of the tensor
+    assert st(lambda: plan_of(src[:1], dst)) == B.TPX_ERR_INVALID_ARG
+    # source sub-tensors overlap without being equal
+    bad = pack([[(0, 0, 2, (4, 64, 48), (0, 0, 0), (4, 40, 48), (0, 1, 2))], [(0, 0, 2, (4, 64, 48), (0, 32, 0), (4, 64, 48), (0, 1, 2))]])
+    assert st(lambda: plan_of(bad, dst)) == B.TPX_ERR_INVALID_ARG
+    # two sub-tensors overlap inside one rank buffer
+    e = src[0][0][0]
+    clash = [([e, e._replace(tensor_id=1)], src[0][1])]
+    assert st(lambda: plan_of(clash, clash)) == B.TPX_ERR_INVALID_ARG
+    # a lost rank without a replica
+    assert st(lambda: plan_of(src, dst, src_alive=[1, 0])) == B.TPX_ERR_UNRECOVERABLE
+    # malformed entries
+    assert st(lambda: plan_of([([e._replace(perm=(0, 0, 2))], src[0][1])], dst)) == B.TPX_ERR_INVALID_ARG
+    assert st(lambda: plan_of([([e._replace(hi=(4, 99, 48))], src[0][1])], dst)) == B.TPX_ERR_INVALID_ARG
+    assert st(lambda: plan_of([([e._replace(elem_bytes=3)], src[0][1])], dst)) == B.TPX_ERR_INVALID_ARG
+
+
+def test_lost_rank_with_replica_is_recovered():
+    src = replicated(2, sequence(2))           # ranks 0,1 and their copies 2,3
+    dst = sequence(4)
+    a = H.np_bufs(src_buffers(src, 3))
+    want = oreshard.reshard_ptc(src, dst, a)
+    plan = plan_of(src, dst, src_alive=[0, 1, 1, 0])
+    assert {b.src_rank for b in plan.boxes()} == {1, 2}
+    a[0][:] = 0xEE
+    a[3][:] = 0xEE
+    got = [np.full(n, H.POISON, dtype=np.uint8) for _, n in dst]
+    host_exec.run_boxes(plan, a, got)
+    assert all(np.array_equal(g, w) for g, w in zip(got, want))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name", list(CASES))
+def test_generic_gpu_matches_oracle(cuda, name):
+    from tests import gpu_util as G
+    print("case", name, flush=True)
+    src, dst = CASES[name]
+    a = src_buffers(src, 9)
+    want = oreshard.reshard_ptc(src, dst, H.np_bufs(a))
+    tpx.tpx_set_option("tile_bytes", 8192)
+    try:
+        plan = plan_of(src, dst)
+    finally:
+        tpx.tpx_set_option("tile_bytes", 131072)
+    got, _ = G.execute(plan, [x.cuda() for x in a])
+    torch.cuda.synchronize()
+    for r in range(len(dst)):
+        assert np.array_equal(got[r].cpu().numpy(), want[r]), r
+
+
+def test_json_configuration_importer():
+    """Two per-GPU JSON documents (paper section 5.1) describing a two-matrix model under 2-way tensor
+    parallelism and under 1 GPU; the imported collections re-partition like the oracle says."""
+    import json
+    from paper_2312_05181_amd import ptc_json
+
+    def gpu(t, T):
+        return {"mlp": {"fc1": {"weight": {"full_shape": [64, 32], "offset": [64 // T * t, 0], "shape": [64 // T, 32], "dtype": "bfloat16"},
+                                "bias": {"full_shape": [64], "offset": [64 // T * t], "shape": [64 // T], "dtype": "float32"}},
+                        "fc2": {"weight": {"full_shape": [32, 64], "offset": [0, 64 // T * t], "shape": [32, 64 // T], "dtype": "bfloat16"}}},
+                "ln": {"weight": {"full_shape": [32], "dtype": "float32"}}}
+    src_m, dst_m, src_b, dst_b, names = ptc_json.manifests_from_json(json.dumps([gpu(0, 2), gpu(1, 2)]), json.dumps([gpu(0, 1)]))
+    assert names == ["/ln/weight", "/mlp/fc1/bias", "/mlp/fc1/weight", "/mlp/fc2/weight"]
+    to_entries = lambda mans, sizes: [([spec.Entry(*b[:10]) for b in m], n) for m, n in zip(mans, sizes)]
+    src, dst = to_entries(src_m, src_b), to_entries(dst_m, dst_b)
+    mix = ((4, "index"),)
+    a = []
+    for entries, n in src:
+        buf = torch.full((n,), H.SRC_GAP, dtype=torch.uint8)
+        for e in entries:
+            d = H.desc_of(e)
+            synth.fill_buffer(buf, [d], 1, ((d.elem_bytes, "index"),))
+        a.append(buf.numpy())
+    want = oreshard.reshard_ptc(src, dst, a)
+    plan = tpx.tpx_plan_ptc(src_m, dst_m, src_bytes=src_b, dst_bytes=dst_b)
+    got = [np.full(n, H.POISON, dtype=np.uint8) for n in dst_b]
+    host_exec.run_tiles(plan, a, got)
+    assert all(np.array_equal(g, w) for g, w in zip(got, want))

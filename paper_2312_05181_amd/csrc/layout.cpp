@@ -242,16 +242,25 @@ tpx_status check_entries(Side& side) {
 // groups (ranks with identical manifests whose indices form an arithmetic progression).
 tpx_status index_side(Side& side, bool want_groups) {
   side.key_of.clear();
+  side.dense_key.clear();
   side.subs.clear();
+  uint64_t max_tid = 0, max_kind = 0;
+  for (const auto& man : side.ranks)
+    for (const tpx_entry& e : man) { max_tid = std::max<uint64_t>(max_tid, e.tensor_id); max_kind = std::max<uint64_t>(max_kind, e.kind); }
+  side.dense_kinds = (max_tid + 1) * (max_kind + 1) <= (1u << 22) ? uint32_t(max_kind + 1) : 0;
+  if (side.dense_kinds) side.dense_key.assign(size_t((max_tid + 1) * side.dense_kinds), -1);
   for (uint32_t r = 0; r < side.ranks.size(); ++r)
     for (uint32_t i = 0; i < side.ranks[r].size(); ++i) {
       const tpx_entry& e = side.ranks[r][i];
-      auto it = side.key_of.find(tensor_key(e));
-      if (it == side.key_of.end()) {
-        it = side.key_of.emplace(tensor_key(e), uint32_t(side.subs.size())).first;
+      int32_t key = side.find_key(e.tensor_id, e.kind);
+      if (key < 0) {
+        key = int32_t(side.subs.size());
+        if (side.dense_kinds) side.dense_key[size_t(e.tensor_id) * side.dense_kinds + e.kind] = key;
+        else side.key_of.emplace((uint64_t(e.tensor_id) << 8) | e.kind, uint32_t(key));
         side.subs.emplace_back();
+        side.subs.back().reserve(side.tp_degree ? side.tp_degree : 4);
       }
-      auto& subs = side.subs[it->second];
+      auto& subs = side.subs[size_t(key)];
       if (!subs.empty()) {
         const tpx_entry& f = side.ranks[subs[0].holders[0].rank][subs[0].holders[0].entry];
         bool same = f.ndim == e.ndim && f.elem_bytes == e.elem_bytes;

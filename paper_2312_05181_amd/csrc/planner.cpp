@@ -51,17 +51,19 @@ tpx_box lower_piece(const uint64_t lo[4], const uint64_t hi[4], const tpx_entry*
   b.dst_rank_stride = 0;
   b.dst_off = de.offset;
   b.src_off = se ? se->offset : 0;
-  std::vector<Axis> ax;
+  Axis ax[4];
+  size_t n = 0;
   for (uint32_t k = 0; k < de.ndim; ++k) {
     b.dst_off += (lo[k] - de.lo[k]) * dstr[k] * eb;
     if (se) b.src_off += (lo[k] - se->lo[k]) * sstr[k] * eb;
-    if (hi[k] - lo[k] > 1) ax.push_back({hi[k] - lo[k], (se ? sstr[k] : dstr[k]) * eb, dstr[k] * eb});
+    if (hi[k] - lo[k] > 1) ax[n++] = Axis{hi[k] - lo[k], (se ? sstr[k] : dstr[k]) * eb, dstr[k] * eb};
   }
-  std::sort(ax.begin(), ax.end(), [](const Axis& x, const Axis& y) { return x.ds != y.ds ? x.ds > y.ds : x.ss > y.ss; });
-  for (size_t i = 0; i + 1 < ax.size();) {
+  std::sort(ax, ax + n, [](const Axis& x, const Axis& y) { return x.ds != y.ds ? x.ds > y.ds : x.ss > y.ss; });
+  for (size_t i = 0; i + 1 < n;) {
     if (ax[i].ss == ax[i + 1].ss * ax[i + 1].extent && ax[i].ds == ax[i + 1].ds * ax[i + 1].extent) {
       ax[i + 1].extent *= ax[i].extent;
-      ax.erase(ax.begin() + long(i));
+      for (size_t j = i; j + 1 < n; ++j) ax[j] = ax[j + 1];
+      --n;
       if (i) --i;
     } else {
       ++i;
@@ -69,14 +71,14 @@ tpx_box lower_piece(const uint64_t lo[4], const uint64_t hi[4], const tpx_entry*
   }
   b.run_bytes = eb;
   b.kind = se ? TPX_BOX_COPY : TPX_BOX_FILL;
-  if (!ax.empty() && ax.back().ds == eb && ax.back().ss == eb) {
-    b.run_bytes = ax.back().extent * eb;
-    ax.pop_back();
-  } else if (!ax.empty() && se) {
+  if (n && ax[n - 1].ds == eb && ax[n - 1].ss == eb) {
+    b.run_bytes = ax[n - 1].extent * eb;
+    --n;
+  } else if (n && se) {
     b.kind = TPX_BOX_TRANSPOSE;
   }
-  b.ndim = uint32_t(ax.size());
-  for (size_t i = 0; i < ax.size(); ++i) {
+  b.ndim = uint32_t(n);
+  for (size_t i = 0; i < n; ++i) {
     b.extent[i] = ax[i].extent;
     b.src_stride[i] = se ? ax[i].ss : 0;
     b.dst_stride[i] = ax[i].ds;
@@ -165,9 +167,9 @@ tpx_status plan_model_moves(tpx_plan_s& plan) {
     for (uint32_t dn = 0; dn < g.count; ++dn) {
       const uint32_t rn = r0 + dn * g.stride;
       for (const tpx_entry& sn : Sn.ranks[r0]) {
-        const auto key = S.key_of.find(tensor_key(sn));  // get_base_tensor: the same tensor, old side
-        if (key == S.key_of.end()) return fail(TPX_ERR_INVALID_ARG, "tensor " + std::to_string(sn.tensor_id) + " is missing from the source configuration");
-        const auto& subs = S.subs[key->second];
+        const int32_t key = S.find_key(sn.tensor_id, sn.kind);  // get_base_tensor: the same tensor, old side
+        if (key < 0) return fail(TPX_ERR_INVALID_ARG, "tensor " + std::to_string(sn.tensor_id) + " is missing from the source configuration");
+        const auto& subs = S.subs[size_t(key)];
         const tpx_entry& any = S.ranks[subs[0].holders[0].rank][subs[0].holders[0].entry];
         tpx_status st = for_each_piece(sn, any, subs, [&](const uint64_t*, const uint64_t*, const SubTensor* sub) -> tpx_status {
           if (!sub) { choice[dn].push_back(-1); return TPX_OK; }
@@ -189,7 +191,7 @@ tpx_status plan_model_moves(tpx_plan_s& plan) {
       const uint32_t rn = r0 + d0 * g.stride;
       size_t cursor = 0;
       for (const tpx_entry& sn : Sn.ranks[rn]) {
-        const auto& subs = S.subs[S.key_of.find(tensor_key(sn))->second];
+        const auto& subs = S.subs[size_t(S.find_key(sn.tensor_id, sn.kind))];
         const tpx_entry& any = S.ranks[subs[0].holders[0].rank][subs[0].holders[0].entry];
         tpx_status st = for_each_piece(sn, any, subs, [&](const uint64_t* lo, const uint64_t* hi, const SubTensor* sub) -> tpx_status {
           const int h = choice[d0][cursor++];

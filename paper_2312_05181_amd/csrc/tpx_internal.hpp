@@ -35,9 +35,21 @@ struct Holder {
 
 // One distinct sub-tensor of a state tensor (a box of the full tensor) and every rank that stores it
 // (data-parallel replicas, replicated tensors, tied copies), in ascending rank order.
+struct HolderList {  // the first two holders inline: most sliced sub-tensors have one or two
+  uint32_t n = 0;
+  Holder inl[2] = {{0, 0}, {0, 0}};
+  std::vector<Holder> more;
+  void push_back(Holder h) {
+    if (n < 2) inl[n] = h; else more.push_back(h);
+    ++n;
+  }
+  size_t size() const { return n; }
+  const Holder& operator[](size_t i) const { return i < 2 ? inl[i] : more[i - 2]; }
+};
+
 struct SubTensor {
   uint64_t lo[4] = {0, 0, 0, 0}, hi[4] = {0, 0, 0, 0};
-  std::vector<Holder> holders;
+  HolderList holders;
 };
 
 // Ranks of the new configuration that hold identical sub-collections at identical offsets
@@ -54,11 +66,21 @@ struct Side {
   std::vector<uint64_t> bytes;                // size of every rank buffer
   // index, built by index_side(): state tensor (tensor_id, kind) -> dense key -> its distinct sub-tensors,
   // sorted by position
-  std::unordered_map<uint64_t, uint32_t> key_of;
+  std::unordered_map<uint64_t, uint32_t> key_of;   // used when the ids are too sparse for the dense table
+  std::vector<int32_t> dense_key;                  // [tensor_id * n_kinds + kind] -> key, -1 = absent
+  uint32_t dense_kinds = 0;                        // 0 = dense table not in use
   std::vector<std::vector<SubTensor>> subs;
+  // key of state tensor (tensor_id, kind), or -1
+  int32_t find_key(uint32_t tensor_id, uint32_t kind) const {
+    if (dense_kinds) {
+      const uint64_t i = uint64_t(tensor_id) * dense_kinds + kind;
+      return kind < dense_kinds && i < dense_key.size() ? dense_key[size_t(i)] : -1;
+    }
+    const auto it = key_of.find((uint64_t(tensor_id) << 8) | kind);
+    return it == key_of.end() ? -1 : int32_t(it->second);
+  }
   std::vector<ReplicaGroup> groups;           // partition of the ranks into replica groups
 };
-inline uint64_t tensor_key(const tpx_entry& e) { return (uint64_t(e.tensor_id) << 8) | e.kind; }
 tpx_status check_entries(Side& side);  // validates every manifest entry, fills nbytes
 tpx_status index_side(Side& side, bool want_groups);  // builds key_of, subs (and groups) from ranks
 

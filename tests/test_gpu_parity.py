@@ -293,3 +293,34 @@ def test_tile_order_streams(cuda, streams):
     finally:
         tpx.tpx_set_option("streams", 4)
         tpx.tpx_set_option("tile_bytes", 131072)
+
+
+def test_execute_inside_a_hip_graph(cuda):
+    """After tpx_prepare, tpx_execute is a single kernel launch on the caller's stream, so it can be captured
+    in a HIP graph and replayed; every replay (with the program's own work in between) must reproduce the
+    eager result for the data then in the source buffers."""
+    model, mix = WIDE, synth.MIX_GPT
+    a, b = Parallel(2, 2, 1), Parallel(4, 1, 2)
+    plan = plan_for(model, a, b)
+    src = [x.cuda() for x in H.make_src_bufs(model, a, 9, mix)]
+    dst = [G.alloc(plan.buffer_bytes(1, r), H.POISON) for r in range(b.n_ranks)]
+    ws = G.alloc(plan.workspace_bytes())
+    side = torch.cuda.Stream()
+    plan.prepare(ws.data_ptr(), side.cuda_stream)
+    sp, dp = [x.data_ptr() for x in src], [x.data_ptr() for x in dst]
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        plan.execute(sp, dp, ws.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    for seed in (9, 10, 11):
+        fresh = H.make_src_bufs(model, a, seed, mix)
+        for x, y in zip(src, fresh):
+            x.copy_(y)
+        for d in dst:
+            d.fill_(H.POISON)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        want = oreshard.reshard(model, a, b, H.np_bufs(fresh))
+        for r in range(b.n_ranks):
+            assert np.array_equal(dst[r].cpu().numpy(), want[r]), (seed, r)

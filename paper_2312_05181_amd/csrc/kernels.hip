@@ -2,11 +2,12 @@
 // re-partition and merge operations of section 4.2) with one kernel launch.
 //
 // The plan reaches the GPU as a small table of flat boxes with the prefix sums of their tile counts;
-// workgroup b finds the box that owns tile b by a short search and derives the tile from the box's
+// a workgroup finds the box that owns its tile by a short search and derives the tile from the box's
 // tiling parameters.  A tile is a bounded piece (at most `tile_bytes`) of one move, so every workgroup has
-// about the same amount of work no matter how uneven the moves are.  Nothing is contracted, so there is no MFMA work: the kernel is a
-// gather/scatter of 16-byte vectors and is bound by HBM bandwidth.  Each thread keeps several independent
-// 16-byte loads in flight before storing them.  LDS is used only by transposing tiles.
+// about the same amount of work no matter how uneven the moves are.  Nothing is contracted, so there is
+// no MFMA work: the kernel is a gather/scatter of 16-byte vectors and is bound by HBM bandwidth.  A
+// workgroup loads its whole tile (threads x loads in flight x 16 bytes), then stores it.  LDS holds only
+// the segment table of merge tiles and the staging array of transposing tiles.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -15,7 +16,6 @@
 #include "tpx_internal.hpp"
 
 namespace {
-
 
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
@@ -248,7 +248,7 @@ __global__ __launch_bounds__(kThreads) void tpx_execute_tiles(const tpx::FlatBox
                                                               uint32_t n_tiles, uint32_t streams, PtrTable ptrs) {
   extern __shared__ __align__(16) uint8_t lds_raw[];
   __shared__ SegLds lseg[kMaxSegLds];
-  // locate this workgroup's tile: uniform for the whole workgroup, so these are scalar loads
+  // Locate this workgroup's tile; everything here is uniform for the workgroup, so these are scalar loads.
   // With `streams` = S > 1 the tile numbers are permuted so that workgroup b works on stream b % S, each
   // stream being a contiguous 1/S of the tile sequence (gridDim.x is a multiple of S then).  The workgroups
   // in flight at any moment then touch S distant regions of the rank buffers instead of one, which spreads

@@ -2,15 +2,17 @@
 // every resource is a buffer in one GPU's memory.
 //
 // The algorithm's three operations collapse into one record per piece:
-//   split(v, sigma, sigma')   - cut points of the old and the new slicing on the sliced axis give the
-//                               pieces w of a tensor that are contiguous in both an old and a new sub-tensor;
+//   split(v, sigma, sigma')   - the pieces w of a tensor are the non-empty intersections of an old and a
+//                               new sub-tensor (boxes of the full tensor);
 //   move(w, r_w, r')          - r_w = get_resource(phi, alpha, w) is a surviving holder of w under the old
 //                               configuration, chosen for locality; r' is the new holder;
 //   merge(W)                  - the pieces of a new sub-tensor are adjacent again simply because each is
 //                               written at its own offset inside the new sub-tensor; nothing is staged.
-// The result is a list of boxes (tpx_box), then cut into equal-byte tiles for the GPU.
+//                               Where the pieces are equal column blocks of the same rows, the GPU tile
+//                               covers whole destination rows and reads all of them (a merge tile).
+// The result is a list of boxes (tpx_box), which tile_boxes() turns into the flat-box table the kernel
+// derives its equal-byte tiles from.
 #include <algorithm>
-#include <chrono>
 #include <cstring>
 
 #include "tpx_internal.hpp"

@@ -100,13 +100,15 @@ def values(seed: int, tensor_id: int, kind: int, stream: str, elem_bytes: int,
     """
     if stream == "index":
         bits = lin + _s64(tensor_id * 0x9E3779B1 + kind * 0x85EBCA6B)
+        if elem_bytes == 1:
+            return ((bits & 0xFF) - ((bits & 0x80) << 1)).to(torch.int8)
         if elem_bytes == 2:
             return ((bits & 0xFFFF) - ((bits & 0x8000) << 1)).to(torch.int16)
         if elem_bytes == 4:
             return ((bits & 0xFFFFFFFF) - ((bits & 0x80000000) << 1)).to(torch.int32)
         if elem_bytes == 8:
             return bits
-        raise ValueError("index stream: element bytes must be 2, 4 or 8")
+        raise ValueError("index stream: element bytes must be 1, 2, 4 or 8")
     if stream == "bf16w":
         return values(seed, tensor_id, kind + 1, "n02", 4, lin).to(torch.bfloat16)
     h = hash64(stream_key(seed, tensor_id, kind), lin)

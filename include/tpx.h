@@ -162,7 +162,12 @@ typedef struct {
   uint64_t plan_ns;           /* host time spent in tpx_plan */
 } tpx_stats_t;
 
-/* Plan the transformation of the model state of `model` from configuration src to dst (algorithm 1).
+/* Plan the transformation of the model state of `model` from configuration src to dst (section 4.2,
+ * algorithm 1: split, re-partition, merge).  Host only; all arguments are HOST pointers read during the
+ * call (nothing is retained).  On success *out owns the plan until tpx_free().  The plan fixes the layout
+ * of every rank buffer of both sides (tpx_buffer_bytes, tpx_manifest): rank (t, p, d) is buffer
+ * t + T*(d + D*p); inside it one arena per state kind, each holding the stage's tensors in the order
+ * embeddings, layers ascending (12 tensors each), final LayerNorm, 256-byte aligned.
  * Errors: INVALID_ARG (NULL, zero degree, > TPX_MAX_RANKS ranks, element size not 1/2/4/8),
  * INDIVISIBLE, BAD_STAGE_MAP, UNRECOVERABLE (src->rank_alive leaves a tensor without holder), OOM. */
 tpx_status tpx_plan(const tpx_model* model, const tpx_parallel* src, const tpx_parallel* dst, tpx_plan_t** out);
@@ -202,7 +207,11 @@ tpx_status tpx_plan_dataset(uint64_t n_samples, uint32_t global_batch, uint32_t 
                             uint32_t D_src, uint32_t D_dst, const uint64_t* src_cursors,
                             uint64_t* dst_cursors, tpx_plan_t** out);
 
-/* Queries (cheap, host only). side: TPX_SIDE_SRC / TPX_SIDE_DST. Out-of-range indices give 0 / INVALID_ARG. */
+/* Queries (cheap, host only; the plan is not modified and nothing is allocated for the caller).
+ * side: TPX_SIDE_SRC / TPX_SIDE_DST.  Out-of-range indices give 0 / INVALID_ARG.  tpx_manifest lists the
+ * sub-tensors of a rank buffer (section 5.2's tree of a state partition, flattened); tpx_get_box the moves
+ * of the plan; tpx_get_tile / tpx_get_segment what workgroup-sized unit of work number i does, computed by
+ * the code the kernel itself uses.  Dataset plans have buffers but no manifest entries. */
 uint32_t   tpx_num_buffers(const tpx_plan_t*, int side);
 uint64_t   tpx_buffer_bytes(const tpx_plan_t*, int side, uint32_t rank);
 uint32_t   tpx_num_entries(const tpx_plan_t*, int side, uint32_t rank);
@@ -240,7 +249,11 @@ tpx_status tpx_prepare(tpx_plan_t*, void* workspace, void* hip_stream);
 /* Forget which workspace holds the plan tables (call after overwriting or freeing it). */
 void tpx_workspace_forget(tpx_plan_t*);
 
+/* Release a plan (NULL is allowed).  The caller must make sure no tpx_execute launch of it is still being
+ * issued; kernels already launched do not need the host plan. */
 void tpx_free(tpx_plan_t*);
+
+/* Description of the last failure on the calling thread (never NULL; valid until that thread's next failure). */
 const char* tpx_last_error(void);
 
 /* Global tuning knobs, read by later tpx_plan / tpx_execute calls on any thread:
@@ -252,6 +265,8 @@ const char* tpx_last_error(void);
  *   "streams"     tile order (1 .. 1024; default 4): workgroup b executes the (b / streams)-th tile of the
  *                 (b % streams)-th contiguous part of the plan, so concurrent workgroups touch `streams`
  *                 distant regions of the buffers
+ *   "max_multicast"  most replicas one move may be written to (1 .. 128; default 8; 1 = every replica is
+ *                 copied separately)
  * Errors: INVALID_ARG for an unknown key or a value out of range. */
 tpx_status tpx_set_option(const char* key, uint64_t value);
 

@@ -265,3 +265,63 @@ def test_json_configuration_importer():
     got = [np.full(n, H.POISON, dtype=np.uint8) for n in dst_b]
     host_exec.run_tiles(plan, a, got)
     assert all(np.array_equal(g, w) for g, w in zip(got, want))
+
+
+def _fig5_collection():
+    """The collection of paper figure 5, built from the fixture: data tensors t1, t2 (a sample batch each) and
+    model tensors t3, t4 (sliced in two along axis 0), one unified collection of tensors."""
+    import os
+    shapes = {"t1": (4, 16), "t2": (4, 16), "t3": (8, 6), "t4": (10, 4)}
+    ids = {"t1": 1, "t2": 2, "t3": 3, "t4": 4}
+    ranks = []
+    with open(os.path.join(os.path.dirname(__file__), "golden", "fig5_tp2_dp2.txt")) as f:
+        for line in f:
+            line = line.split("#")[0].split()
+            if not line:
+                continue
+            per = []
+            data = line[1]
+            per.append((ids[data], 0, 4, shapes[data], (0, 0), shapes[data], (0, 1)))
+            for sub in line[2:]:
+                name, part = sub.split("^")
+                full = shapes[name]
+                a, b = even(full[0], 2, int(part) - 1)
+                per.append((ids[name], 0, 4, full, (a, 0), (b, full[1]), (0, 1)))
+            ranks.append(per)
+    return pack(ranks)
+
+
+def test_fig5_unified_collection_reconfigures():
+    """Figure 5's collection (data and model state as one tensor collection) against this library's rank
+    order, and its reconfiguration to data parallelism only (4 GPUs, full model each, half a batch each)."""
+    src = _fig5_collection()
+    assert len(src) == 4
+    # alpha of this library: rank = t + T*d reproduces the figure's R1..R4 (cross product of data and model parts)
+    for r, (entries, _) in enumerate(src):
+        t, d = r % 2, r // 2
+        assert entries[0].tensor_id == 1 + d                                  # data sub-collection of replica d
+        assert all(e.lo[0] == even(e.full_shape[0], 2, t)[0] for e in entries[1:])   # model part t
+    plan_same = plan_of(src, src)
+    assert plan_same.stats()["bytes_cross_rank"] == 0
+    # new configuration: no tensor parallelism, 4 data-parallel replicas, each data tensor cut in two sample halves
+    ranks = []
+    for r in range(4):
+        data_id, half = 1 + r // 2, r % 2
+        per = [(data_id, 0, 4, (4, 16), (2 * half, 0), (2 * half + 2, 16), (0, 1))]
+        per += [(3, 0, 4, (8, 6), (0, 0), (8, 6), (0, 1)), (4, 0, 4, (10, 4), (0, 0), (10, 4), (0, 1))]
+        ranks.append(per)
+    dst = pack(ranks)
+    mix = ((4, "index"),)
+    a = []
+    for entries, n in src:
+        b = torch.full((n,), H.SRC_GAP, dtype=torch.uint8)
+        synth.fill_buffer(b, [H.desc_of(e) for e in entries], 2, mix)
+        a.append(b.numpy())
+    want = oreshard.reshard_ptc(src, dst, a)
+    plan = plan_of(src, dst)
+    got = [np.full(n, H.POISON, dtype=np.uint8) for _, n in dst]
+    host_exec.run_tiles(plan, a, got)
+    assert all(np.array_equal(g, w) for g, w in zip(got, want))
+    # every model tensor is merged from its two halves; every data half is taken from the GPU's own copy of the batch
+    assert {(b.src_rank, b.dst_rank) for b in plan.boxes() if b.tensor_id in (1, 2)} == {(0, 0), (1, 1), (2, 2), (3, 3)}
+    assert {b.src_rank for b in plan.boxes() if b.tensor_id == 3 and b.dst_rank == 0} == {0, 1}

@@ -398,15 +398,19 @@ tpx_status hip_launch_tiles(const void* workspace, const tpx_plan_s& plan, const
   }
   const WorkspaceLayout w = workspace_layout(plan);
   const uint8_t* base = static_cast<const uint8_t*>(workspace);
-  if (variant == 0) {
-    // automatic: a workgroup should load its whole tile at once (threads x loads in flight x 16 bytes = tile)
-    variant = plan.tile_bytes_used >= 131072 ? (3 | 24 | (2 << 5))   // 1024 threads x 8
+  const bool automatic = variant == 0;
+  if (automatic) {
+    // a workgroup should load its whole tile at once (threads x loads in flight x 16 bytes = tile); transposing
+    // tiles serialise load / LDS / store phases inside a workgroup, so they want several small workgroups
+    // per CU to overlap each other
+    variant = plan.needs_lds                 ? (2 | 24)              //  256 threads x 4
+            : plan.tile_bytes_used >= 131072 ? (3 | 24 | (2 << 5))   // 1024 threads x 8
             : plan.tile_bytes_used >= 65536  ? (3 | 24 | (1 << 5))   //  512 threads x 8
                                              : (2 | 24);             //  256 threads x 4 (small jobs, small tiles)
   }
   // interleaving several parts of the plan pays only when tiles cost the same; a plan that mixes plain and
-  // replicated moves runs in plan order
-  const uint32_t streams = plan.uniform_tiles ? uint32_t(std::max<uint64_t>(1, tuning().streams)) : 1;
+  // replicated moves, or has transposing tiles, runs in plan order
+  const uint32_t streams = plan.uniform_tiles && !(automatic && plan.needs_lds) ? uint32_t(std::max<uint64_t>(1, tuning().streams)) : 1;
   const uint32_t grid = uint32_t((plan.n_tiles + streams - 1) / streams * streams);
   KernelFn k = pick_kernel(variant);
   hipLaunchKernelGGL(k, dim3(grid), dim3(threads_of(variant)), plan.needs_lds ? kLdsBytes : 0,

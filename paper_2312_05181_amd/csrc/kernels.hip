@@ -358,17 +358,6 @@ KernelFn pick_kernel(uint64_t variant) {
 
 namespace tpx {
 
-WorkspaceLayout workspace_layout(const tpx_plan_s& plan) {
-  auto up = [](uint64_t x) { return (x + 255) / 256 * 256; };
-  WorkspaceLayout w;
-  w.boxes_off = 0;
-  w.first_off = up(plan.flat.size() * sizeof(FlatBox));
-  w.coarse_off = w.first_off + up(plan.first_tile.size() * sizeof(uint32_t));
-  w.seg_off = w.coarse_off + up(plan.coarse.size() * sizeof(uint32_t));
-  w.total = std::max<uint64_t>(256, w.seg_off + up(plan.segments.size() * sizeof(tpx_segment)));
-  return w;
-}
-
 tpx_status hip_upload_tables(void* workspace, const tpx_plan_s& plan, void* stream) {
   hipStream_t st = static_cast<hipStream_t>(stream);
   const WorkspaceLayout w = workspace_layout(plan);

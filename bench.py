@@ -72,8 +72,16 @@ DATASET_WORKLOAD = "dataset_1e8_D6->D4"
 DATASET_CFG = dict(n_samples=10 ** 8, global_batch=768, D_src=6, D_dst=4, steps_done=65000, seed=6)
 DEFAULT_WORKLOAD = "gpt6.7b_(8,1,1)->(1,8,1)"
 
-# HBM bytes per launch of the copy kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE runs, or None.
-MEASURED_TRAFFIC = {"gpt6.7b_(8,1,1)->(1,8,1)": 186355265353}
+# HBM bytes per launch of the copy kernel, measured with rocprofv3 FETCH_SIZE / WRITE_SIZE passes scaled by a plain
+# copy of known size (the summaries under profiles/ give the raw counter values), or None where not measured.
+MEASURED_TRAFFIC = {
+    "gpt6.7b_(8,1,1)->(1,8,1)": 186355265353,
+    "gpt1.3b_(4,2,1)->(2,4,1)": 36857000000,
+    "gpt2.7b_(4,4,2)->(2,4,1)": 74272000000,
+    "gpt_h3072_T3->T4_padded_vocab": 80869000000,
+    "gpt1.3b_(4,2,1)->(4,2,2)_dp": 55528000000,
+    "gpt1.3b_(4,2,1)->(2,4,1)_transposed_dst": 36855000000,
+}
 
 
 def main() -> int:

@@ -319,3 +319,19 @@ def test_row_parallel_merges_become_merge_tiles():
     # a 3 -> 4 re-slicing has unequal pieces per destination row: those stay one tile per move
     model5, src5, dst5, _, _ = H.CONFIGS[5]
     assert len(plan_for(model5, src5, dst5).segments()) == 0
+
+
+def test_command_line_front_end():
+    import json
+    import subprocess
+    import sys
+    base = [sys.executable, "-m", "paper_2312_05181_amd"]
+    args = ["--layers", "2", "--hidden", "256", "--heads", "4", "--ffn", "1024", "--vocab", "1024", "--state-bytes", "4,4,4",
+            "--src", "2,1,1", "--dst", "4,2,1"]
+    out = subprocess.run(base + ["plan"] + args, cwd=ROOT, capture_output=True, text=True, check=True).stdout
+    st = json.loads(out)
+    assert st["bytes_written"] == oreshard.state_bytes(H.TINY, Parallel(4, 2, 1)) and len(st["dst_buffer_bytes"]) == 8
+    out = subprocess.run(base + ["manifest"] + args + ["--side", "dst", "--rank", "7"], cwd=ROOT, capture_output=True, text=True, check=True).stdout
+    assert "/7/layer1/attention.query_key_value.weight[kind 0]" in out and "final_layernorm.bias" in out
+    bad = subprocess.run(base + ["plan"] + args[:-1] + ["3,1,1"], cwd=ROOT, capture_output=True, text=True)
+    assert bad.returncode == 1 and "tpx status -2" in bad.stderr

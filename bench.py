@@ -197,7 +197,7 @@ def main() -> int:
                 "kernel": "tpx_execute_tiles", "kernel_ms_avg": round(kernel_ms_avg, 4),
                 "kernel_ms_min": round(min(kernel_ms), 4), "algorithmic_bytes_per_launch": state_bytes}
 
-    probe = None
+    probe = memcpy_probe = None
     if not args.no_probe:
         n = min(8 << 30, min(b.numel() for b in src_bufs if b.numel()) // 16 * 16, dst_bufs[0].numel() // 16 * 16)
         a, b = src_bufs[0], dst_bufs[0]
@@ -210,6 +210,15 @@ def main() -> int:
         e1.record()
         torch.cuda.synchronize()
         probe = round(2 * n * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+        # the runtime's own device-to-device copy of the same bytes (torch issues a hipMemcpyAsync for it)
+        for _ in range(2):
+            b[:n].copy_(a[:n])
+        e0.record()
+        for _ in range(5):
+            b[:n].copy_(a[:n])
+        e1.record()
+        torch.cuda.synchronize()
+        memcpy_probe = round(2 * n * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
 
     cpu = None
     if args.cpu_layers > 0:
@@ -231,6 +240,7 @@ def main() -> int:
                             "isolated_plan_upload_kernel": round(latency_ms, 4),
                             "back_to_back_step": round(ms_per_step, 4)},
         "copy_probe_GBps": probe,
+        "memcpy_d2d_GBps": memcpy_probe,
         "setup_s": round(setup_s, 1),
         "roofline": roofline,
         "cpu_baseline": cpu,
@@ -318,6 +328,17 @@ def bench_dataset(args) -> int:
     return 0
 
 
+def _cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(args, model, src, dst, plan, src_bufs, dst_bufs, src_ptrs, dst_ptrs, ws, stream):
     """Time the CPU oracle (numpy: paste the old shards into the full tensor, slice it anew) on the state
     tensors of the first `--cpu-layers` layers, threaded over tensors; check the GPU result against it."""
@@ -370,7 +391,8 @@ def cpu_baseline(args, model, src, dst, plan, src_bufs, dst_bufs, src_ptrs, dst_
             "sample": f"all state tensors of the first {layers} of {om.n_layers} layers "
                       f"({moved / 2e9:.2f} GB read + the same written), numpy, {threads} threads over tensors, "
                       f"mean of {passes} passes",
-            "seconds": round(secs, 2), "gpu_matches_oracle_on_sample": ok}
+            "seconds": round(secs, 2), "host_cpus_online": os.cpu_count(), "host_cpu_model": _cpu_model(),
+            "gpu_matches_oracle_on_sample": ok}
 
 
 if __name__ == "__main__":

@@ -42,6 +42,7 @@ typedef enum {
   TPX_ERR_BAD_STAGE_MAP = -3, /* stage boundaries not ascending from 0 to n_layers */
   TPX_ERR_OOM = -4,           /* host allocation failed */
   TPX_ERR_HIP = -5,           /* a HIP runtime call failed (message has the HIP error) */
+  TPX_ERR_STALE_WORKSPACE = -6, /* the workspace does not (or no longer) hold this plan's tables */
   TPX_ERR_CURSOR = -7,        /* dataset cursors are not those of a whole number of steps */
   TPX_ERR_UNRECOVERABLE = -8  /* some state has no surviving source holder */
 } tpx_status;
@@ -225,7 +226,8 @@ tpx_status tpx_get_tile(const tpx_plan_t*, uint64_t i, tpx_tile* out);
 uint64_t   tpx_num_segments(const tpx_plan_t*);
 tpx_status tpx_get_segment(const tpx_plan_t*, uint64_t i, tpx_segment* out);
 
-/* DEVICE bytes tpx_execute needs in `workspace` (the plan tables: flat boxes and tile prefix sums). */
+/* DEVICE bytes tpx_execute needs in `workspace` (a header, then the plan tables: flat boxes, tile prefix
+ * sums, merge segments). */
 uint64_t   tpx_workspace_bytes(const tpx_plan_t*);
 
 /* Apply the plan (section 5.1, step 4): one kernel launch on `hip_stream` (a hipStream_t, NULL = the
@@ -248,6 +250,14 @@ tpx_status tpx_prepare(tpx_plan_t*, void* workspace, void* hip_stream);
 
 /* Forget which workspace holds the plan tables (call after overwriting or freeing it). */
 void tpx_workspace_forget(tpx_plan_t*);
+
+/* The tables start with a header stamped with an id unique to the plan, and the kernel compares it with
+ * the plan it was launched for: a tpx_execute on a workspace that another plan's tables (or anything
+ * else) have overwritten since the upload moves nothing instead of following foreign tables.  This call
+ * tells the caller about it: it waits for `hip_stream`, reads the header back and returns
+ * TPX_ERR_STALE_WORKSPACE unless it is this plan's.  Use it after tpx_execute when the workspace's
+ * history is in doubt.  Errors: INVALID_ARG, HIP, STALE_WORKSPACE. */
+tpx_status tpx_workspace_check(const tpx_plan_t*, const void* workspace, void* hip_stream);
 
 /* Release a plan (NULL is allowed).  The caller must make sure no tpx_execute launch of it is still being
  * issued; kernels already launched do not need the host plan. */

@@ -23,7 +23,7 @@ _lib = C.CDLL(LIB_PATH)
 
 TPX_OK = 0
 TPX_ERR_INVALID_ARG, TPX_ERR_INDIVISIBLE, TPX_ERR_BAD_STAGE_MAP, TPX_ERR_OOM, TPX_ERR_HIP = -1, -2, -3, -4, -5
-TPX_ERR_CURSOR, TPX_ERR_UNRECOVERABLE = -7, -8
+TPX_ERR_STALE_WORKSPACE, TPX_ERR_CURSOR, TPX_ERR_UNRECOVERABLE = -6, -7, -8
 TPX_MAX_RANKS = 128
 SIDE_SRC, SIDE_DST = 0, 1
 MODEL_TIED_HEAD = 1
@@ -112,6 +112,7 @@ _sigs = {
     "tpx_execute": (C.c_int, [_P, C.POINTER(_P), C.POINTER(_P), _P, _P]),
     "tpx_prepare": (C.c_int, [_P, _P, _P]),
     "tpx_workspace_forget": (None, [_P]),
+    "tpx_workspace_check": (C.c_int, [_P, _P, _P]),
     "tpx_free": (None, [_P]),
     "tpx_last_error": (C.c_char_p, []),
     "tpx_set_option": (C.c_int, [C.c_char_p, C.c_uint64]),
@@ -230,6 +231,10 @@ class Plan:
 
     def workspace_forget(self) -> None:
         _lib.tpx_workspace_forget(self._h)
+
+    def workspace_check(self, workspace_ptr: int, stream: int = 0) -> None:
+        """Wait for the stream and raise TpxError(TPX_ERR_STALE_WORKSPACE) unless the workspace holds this plan."""
+        _check(_lib.tpx_workspace_check(self._h, _P(workspace_ptr), _P(stream)))
 
 
 def tpx_plan(model: dict, src: dict, dst: dict) -> Plan:

@@ -1,7 +1,11 @@
 // C ABI of libtpx (declared in tpx.h): argument checking and hand-off to the planner and the HIP executor.
+#include <atomic>
 #include <chrono>
 #include <cstring>
+#include <memory>
+#include <exception>
 #include <new>
+#include <string>
 
 #include "tpx_internal.hpp"
 
@@ -13,7 +17,20 @@ uint64_t now_ns() {
                       std::chrono::steady_clock::now().time_since_epoch()).count());
 }
 
+// Never 0, different for every plan of this process and unlikely to repeat across processes that share a
+// device buffer: a counter mixed with the time the library was first used.
+uint64_t next_plan_id() {
+  static const uint64_t salt = now_ns();
+  static std::atomic<uint64_t> counter{0};
+  uint64_t x = salt + 0x9e3779b97f4a7c15ull * (counter.fetch_add(1) + 1);
+  x = (x ^ (x >> 30)) * 0xbf58476d1ce4e5b9ull;
+  x = (x ^ (x >> 27)) * 0x94d049bb133111ebull;
+  x ^= x >> 31;
+  return x ? x : 1;
+}
+
 tpx_status finish_plan(tpx_plan_s& p) {
+  p.id = next_plan_id();
   coalesce_boxes(p.boxes);
   if (tpx_status st = tile_boxes(p, tuning().tile_bytes)) return st;
   if (tpx_status st = validate_tiles(p)) return st;
@@ -29,19 +46,21 @@ tpx_status tpx_plan(const tpx_model* model, const tpx_parallel* src, const tpx_p
   const uint64_t t0 = now_ns();
   try {
     if (tpx_status st = check_model(*model)) return st;
-    tpx_plan_s* p = new tpx_plan_s();
+    std::unique_ptr<tpx_plan_s> p(new tpx_plan_s());
     p->model = *model;
     tpx_status st = build_side(*model, *src, p->side[0]);
     if (!st) st = build_side(*model, *dst, p->side[1]);
     if (!st) st = index_side(p->side[1], true);
     if (!st) st = plan_model_moves(*p);
     if (!st) st = finish_plan(*p);
-    if (st) { delete p; return st; }
+    if (st) return st;
     p->stats.plan_ns = now_ns() - t0;
-    *out = p;
+    *out = p.release();
     return TPX_OK;
   } catch (const std::bad_alloc&) {
     return fail(TPX_ERR_OOM, "tpx_plan: out of host memory");
+  } catch (const std::exception& e) {
+    return fail(TPX_ERR_INVALID_ARG, std::string("tpx_plan: ") + e.what());
   }
 }
 
@@ -71,19 +90,21 @@ tpx_status tpx_plan_ptc(const tpx_ptc* src, const tpx_ptc* dst, tpx_plan_t** out
   if (!src || !dst || !out) return fail(TPX_ERR_INVALID_ARG, "tpx_plan_ptc: NULL argument");
   const uint64_t t0 = now_ns();
   try {
-    tpx_plan_s* p = new tpx_plan_s();
+    std::unique_ptr<tpx_plan_s> p(new tpx_plan_s());
     tpx_status st = side_from_ptc(src, p->side[0], "source");
     if (!st) st = side_from_ptc(dst, p->side[1], "destination");
     if (!st) st = index_side(p->side[0], false);
     if (!st) st = index_side(p->side[1], true);
     if (!st) st = plan_model_moves(*p);
     if (!st) st = finish_plan(*p);
-    if (st) { delete p; return st; }
+    if (st) return st;
     p->stats.plan_ns = now_ns() - t0;
-    *out = p;
+    *out = p.release();
     return TPX_OK;
   } catch (const std::bad_alloc&) {
     return fail(TPX_ERR_OOM, "tpx_plan_ptc: out of host memory");
+  } catch (const std::exception& e) {
+    return fail(TPX_ERR_INVALID_ARG, std::string("tpx_plan_ptc: ") + e.what());
   }
 }
 
@@ -92,18 +113,20 @@ tpx_status tpx_plan_dataset(uint64_t n_samples, uint32_t global_batch, uint32_t 
   if (!out || !dst_cursors) return fail(TPX_ERR_INVALID_ARG, "tpx_plan_dataset: NULL argument");
   const uint64_t t0 = now_ns();
   try {
-    tpx_plan_s* p = new tpx_plan_s();
+    std::unique_ptr<tpx_plan_s> p(new tpx_plan_s());
     p->is_dataset = true;
     std::vector<uint64_t> cur;
     tpx_status st = plan_dataset_moves(*p, n_samples, global_batch, index_elem_bytes, D_src, D_dst, src_cursors, cur);
     if (!st) st = finish_plan(*p);
-    if (st) { delete p; return st; }
+    if (st) return st;
     std::copy(cur.begin(), cur.end(), dst_cursors);
     p->stats.plan_ns = now_ns() - t0;
-    *out = p;
+    *out = p.release();
     return TPX_OK;
   } catch (const std::bad_alloc&) {
     return fail(TPX_ERR_OOM, "tpx_plan_dataset: out of host memory");
+  } catch (const std::exception& e) {
+    return fail(TPX_ERR_INVALID_ARG, std::string("tpx_plan_dataset: ") + e.what());
   }
 }
 
@@ -190,6 +213,16 @@ tpx_status tpx_execute(tpx_plan_t* p, const void* const* src_bufs, void* const* 
   if (p->n_tiles == 0) return TPX_OK;
   if (tpx_status st = tpx_prepare(p, workspace, hip_stream)) return st;
   return hip_launch_tiles(workspace, *p, src_bufs, ns, dst_bufs, nd, tuning().variant, hip_stream);
+}
+
+tpx_status tpx_workspace_check(const tpx_plan_t* p, const void* workspace, void* hip_stream) {
+  if (!p || !workspace) return fail(TPX_ERR_INVALID_ARG, "tpx_workspace_check: NULL argument");
+  if (p->n_tiles == 0) return TPX_OK;  // nothing is ever uploaded for an empty plan
+  WorkspaceHeader h{};
+  if (tpx_status st = hip_read_header(workspace, hip_stream, &h)) return st;
+  if (h.plan_id != p->id || h.n_boxes != p->flat.size() || h.n_tiles != p->n_tiles || h.n_segments != p->segments.size())
+    return fail(TPX_ERR_STALE_WORKSPACE, "the workspace does not hold this plan's tables");
+  return TPX_OK;
 }
 
 void tpx_workspace_forget(tpx_plan_t* p) {

@@ -241,13 +241,17 @@ static_assert(kLdsBytes >= TransposeShape<uint8_t>::kBytes && kLdsBytes >= Trans
                   kLdsBytes >= TransposeShape<uint64_t>::kBytes, "LDS budget");
 
 template <int kThreads, int U, bool NTL, bool NTS>
-__global__ __launch_bounds__(kThreads) void tpx_execute_tiles(const tpx::FlatBox* __restrict__ boxes,
+__global__ __launch_bounds__(kThreads) void tpx_execute_tiles(const tpx::WorkspaceHeader* __restrict__ header, uint64_t plan_id,
+                                                              const tpx::FlatBox* __restrict__ boxes,
                                                               const uint32_t* __restrict__ first_tile,
                                                               const uint32_t* __restrict__ coarse,
                                                               const tpx_segment* __restrict__ segs, uint32_t n_boxes,
                                                               uint32_t n_tiles, uint32_t streams, PtrTable ptrs) {
   extern __shared__ __align__(16) uint8_t lds_raw[];
   __shared__ SegLds lseg[kMaxSegLds];
+  // The tables behind `header` must be the ones this launch was made for (a workspace recycled for another
+  // plan since the upload would send the moves anywhere): otherwise the whole grid does nothing.
+  if (header->plan_id != plan_id) return;
   // Locate this workgroup's tile; everything here is uniform for the workgroup, so these are scalar loads.
   // With `streams` = S > 1 the tile numbers are permuted so that workgroup b works on stream b % S, each
   // stream being a contiguous 1/S of the tile sequence (gridDim.x is a multiple of S then).  The workgroups
@@ -318,7 +322,7 @@ tpx_status hip_fail(hipError_t e, const char* what) {
   return tpx::fail(TPX_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
 }
 
-using KernelFn = void (*)(const tpx::FlatBox*, const uint32_t*, const uint32_t*, const tpx_segment*, uint32_t, uint32_t, uint32_t, PtrTable);
+using KernelFn = void (*)(const tpx::WorkspaceHeader*, uint64_t, const tpx::FlatBox*, const uint32_t*, const uint32_t*, const tpx_segment*, uint32_t, uint32_t, uint32_t, PtrTable);
 
 template <int T, int U>
 KernelFn pick_nt(bool nt) {
@@ -362,7 +366,10 @@ tpx_status hip_upload_tables(void* workspace, const tpx_plan_s& plan, void* stre
   hipStream_t st = static_cast<hipStream_t>(stream);
   const WorkspaceLayout w = workspace_layout(plan);
   uint8_t* base = static_cast<uint8_t*>(workspace);
-  hipError_t e = hipMemcpyAsync(base + w.boxes_off, plan.flat.data(), plan.flat.size() * sizeof(FlatBox), hipMemcpyHostToDevice, st);
+  const WorkspaceHeader h{plan.id, plan.flat.size(), plan.n_tiles, plan.segments.size()};
+  hipError_t e = hipMemcpyAsync(base + w.header_off, &h, sizeof(h), hipMemcpyHostToDevice, st);
+  if (e == hipSuccess)
+    e = hipMemcpyAsync(base + w.boxes_off, plan.flat.data(), plan.flat.size() * sizeof(FlatBox), hipMemcpyHostToDevice, st);
   if (e == hipSuccess)
     e = hipMemcpyAsync(base + w.first_off, plan.first_tile.data(), plan.first_tile.size() * sizeof(uint32_t), hipMemcpyHostToDevice, st);
   if (e == hipSuccess)
@@ -403,13 +410,22 @@ tpx_status hip_launch_tiles(const void* workspace, const tpx_plan_s& plan, const
   const uint32_t grid = uint32_t((plan.n_tiles + streams - 1) / streams * streams);
   KernelFn k = pick_kernel(variant);
   hipLaunchKernelGGL(k, dim3(grid), dim3(threads_of(variant)), plan.needs_lds ? kLdsBytes : 0,
-                     static_cast<hipStream_t>(stream), reinterpret_cast<const FlatBox*>(base + w.boxes_off),
+                     static_cast<hipStream_t>(stream), reinterpret_cast<const WorkspaceHeader*>(base + w.header_off),
+                     plan.id, reinterpret_cast<const FlatBox*>(base + w.boxes_off),
                      reinterpret_cast<const uint32_t*>(base + w.first_off),
                      reinterpret_cast<const uint32_t*>(base + w.coarse_off),
                      reinterpret_cast<const tpx_segment*>(base + w.seg_off), uint32_t(plan.flat.size()),
                      uint32_t(plan.n_tiles), streams, pt);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(e, "launching the tile kernel");
+  return TPX_OK;
+}
+
+tpx_status hip_read_header(const void* workspace, void* stream, WorkspaceHeader* out) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipError_t e = hipMemcpyAsync(out, workspace, sizeof(WorkspaceHeader), hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  if (e != hipSuccess) return hip_fail(e, "reading the workspace header");
   return TPX_OK;
 }
 

@@ -455,8 +455,9 @@ tpx_status validate_tiles(tpx_plan_s& plan) {
 WorkspaceLayout workspace_layout(const tpx_plan_s& plan) {
   auto up = [](uint64_t x) { return (x + 255) / 256 * 256; };
   WorkspaceLayout w;
-  w.boxes_off = 0;
-  w.first_off = up(plan.flat.size() * sizeof(FlatBox));
+  w.header_off = 0;
+  w.boxes_off = up(sizeof(WorkspaceHeader));
+  w.first_off = w.boxes_off + up(plan.flat.size() * sizeof(FlatBox));
   w.coarse_off = w.first_off + up(plan.first_tile.size() * sizeof(uint32_t));
   w.seg_off = w.coarse_off + up(plan.coarse.size() * sizeof(uint32_t));
   w.total = std::max<uint64_t>(256, w.seg_off + up(plan.segments.size() * sizeof(tpx_segment)));

@@ -120,6 +120,7 @@ struct tpx_plan_s {
   bool needs_lds = false;       // some tile is staged through LDS
   bool uniform_tiles = true;    // every tile has the same number of destinations (same cost per byte)
   void* uploaded_ws = nullptr;  // device workspace that currently holds the tables
+  uint64_t id = 0;              // process-unique, never 0: stamps the workspace header
 };
 
 namespace tpx {
@@ -136,13 +137,20 @@ tpx_status plan_dataset_moves(tpx_plan_s& plan, uint64_t n_samples, uint32_t B, 
 
 // HIP executor (kernels.hip).
 // Workspace layout: flat boxes, then first_tile, then coarse, then segments, each section starting on a 256-byte boundary.
+// The workspace starts with a 256-byte header whose first word is the id of the plan whose tables
+// follow; the kernel compares it with the id it was launched with and does nothing on a mismatch, so a
+// workspace that was overwritten or recycled since the upload cannot steer it out of bounds.
 struct WorkspaceLayout {
-  uint64_t boxes_off = 0, first_off = 0, coarse_off = 0, seg_off = 0, total = 0;
+  uint64_t header_off = 0, boxes_off = 0, first_off = 0, coarse_off = 0, seg_off = 0, total = 0;
+};
+struct WorkspaceHeader {
+  uint64_t plan_id, n_boxes, n_tiles, n_segments;
 };
 WorkspaceLayout workspace_layout(const tpx_plan_s& plan);
 tpx_status hip_upload_tables(void* workspace, const tpx_plan_s& plan, void* stream);
 tpx_status hip_launch_tiles(const void* workspace, const tpx_plan_s& plan, const void* const* src, uint32_t n_src,
                             void* const* dst, uint32_t n_dst, uint64_t variant, void* stream);
 tpx_status hip_probe_copy(void* dst, const void* src, uint64_t nbytes, void* stream);
+tpx_status hip_read_header(const void* workspace, void* stream, WorkspaceHeader* out);
 
 }  // namespace tpx

@@ -127,6 +127,36 @@ def test_execute_argument_errors(cuda):
     torch.cuda.synchronize()
 
 
+def test_recycled_workspace_moves_nothing_and_is_reported(cuda):
+    """A workspace overwritten by another plan's tables since the upload: the launch must not follow them."""
+    model, mix = SMALL, SMALL_MIX
+    a, b = Parallel(2, 1, 1), Parallel(1, 2, 1)
+    src_cpu = H.make_src_bufs(model, a, 3, mix)
+    want = oreshard.reshard(model, a, b, H.np_bufs(src_cpu))
+    src = [x.cuda() for x in src_cpu]
+    first, other = plan_for(model, a, b), plan_for(model, a, Parallel(2, 2, 1))
+    ws = G.alloc(max(first.workspace_bytes(), other.workspace_bytes()))
+    stream = torch.cuda.current_stream().cuda_stream
+    got, _ = G.execute(first, src, workspace=ws)
+    first.workspace_check(ws.data_ptr(), stream)
+    assert all(np.array_equal(g.cpu().numpy(), w) for g, w in zip(got, want))
+    other.prepare(ws.data_ptr(), stream)                         # the other plan's tables now sit in ws
+    other.workspace_check(ws.data_ptr(), stream)
+    stale, _ = G.execute(first, src, workspace=ws)               # `first` still believes ws is its own
+    with pytest.raises(tpx.TpxError) as err:
+        first.workspace_check(ws.data_ptr(), stream)
+    assert err.value.status == tpx.binding.TPX_ERR_STALE_WORKSPACE
+    assert all(bool((x == H.POISON).all()) for x in stale)       # nothing was written
+    ws.zero_()                                                   # garbage instead of any plan
+    stale, _ = G.execute(first, src, workspace=ws)
+    torch.cuda.synchronize()
+    assert all(bool((x == H.POISON).all()) for x in stale)
+    first.workspace_forget()                                     # told so, it uploads again
+    got, _ = G.execute(first, src, workspace=ws)
+    first.workspace_check(ws.data_ptr(), stream)
+    assert all(np.array_equal(g.cpu().numpy(), w) for g, w in zip(got, want))
+
+
 def test_probe_copy(cuda):
     for n in (16, 4096 + 48, 1 << 24):
         a = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda")

@@ -335,3 +335,18 @@ def test_command_line_front_end():
     assert "/7/layer1/attention.query_key_value.weight[kind 0]" in out and "final_layernorm.bias" in out
     bad = subprocess.run(base + ["plan"] + args[:-1] + ["3,1,1"], cwd=ROOT, capture_output=True, text=True)
     assert bad.returncode == 1 and "tpx status -2" in bad.stderr
+
+
+def test_package_imports_without_the_library_and_fails_loudly_on_use(tmp_path):
+    """A tree without libtpx.so: the package (and so its build module) still imports; any use raises."""
+    import shutil
+    import subprocess
+    import sys
+    pkg = tmp_path / "paper_2312_05181_amd"
+    pkg.mkdir()
+    for f in ("__init__.py", "binding.py", "build.py"):
+        shutil.copy(os.path.join(ROOT, "paper_2312_05181_amd", f), pkg / f)
+    code = ("import paper_2312_05181_amd as t, paper_2312_05181_amd.build\n"
+            "try:\n    t.tpx_plan\nexcept ImportError as e:\n    print('LOUD', e)\n")
+    out = subprocess.run([sys.executable, "-c", code], cwd=tmp_path, capture_output=True, text=True, check=True).stdout
+    assert "LOUD" in out and "no CPU fallback" in out

@@ -100,20 +100,20 @@ def random_collection(rng, tensors, n_ranks):
     return pack(ranks)
 
 
-@pytest.mark.parametrize("seed", range(40))
-def test_random_explicit_collections(seed):
+def random_explicit_case(seed, dims):
+    """Random tensors, each cut into random boxes, spread (some replicated) over random ranks, in random
+    storage orders on both sides; returns (src manifests, dst manifests, src buffers, oracle result)."""
     rng = random.Random(5000 + seed)
     tensors = []
     for _ in range(rng.randrange(1, 5)):
         nd = rng.randrange(1, 5)
-        shape = tuple(rng.choice([1, 2, 3, 5, 8, 16, 24]) for _ in range(nd))
+        shape = tuple(rng.choice(dims) for _ in range(nd))
         kinds = rng.choice([(4,), (2, 4), (8,), (1, 2)])
         perm_src = tuple(rng.sample(range(nd), nd))
         tensors.append((shape, kinds, perm_src))
     src = random_collection(rng, tensors, rng.randrange(1, 5))
     tensors_dst = [(s, k, tuple(rng.sample(range(len(s)), len(s)))) for s, k, _ in tensors]   # any storage order
     dst = random_collection(rng, tensors_dst, rng.randrange(1, 6))
-    mix = {1: "index", 2: "index", 4: "index", 8: "index"}
 
     def fill(man, fill_byte):
         out = []
@@ -127,6 +127,12 @@ def test_random_explicit_collections(seed):
     a = fill(src, H.SRC_GAP)
     want = oreshard.reshard_ptc(src, dst, a)
     assert all(np.array_equal(x, y) for x, y in zip(want, fill(dst, H.POISON)))      # oracle vs value function
+    return src, dst, a, want
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_explicit_collections(seed):
+    src, dst, a, want = random_explicit_case(seed, [1, 2, 3, 5, 8, 16, 24])
     tpx.tpx_set_option("tile_bytes", 4096)
     try:
         plan = plan_of(src, dst)
@@ -137,6 +143,26 @@ def test_random_explicit_collections(seed):
         how(plan, a, got)
         for r in range(len(dst)):
             assert np.array_equal(got[r], want[r]), (seed, r)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dims", [[1, 2, 3, 5, 8, 16, 24], [1, 3, 8, 24, 64, 136, 200]], ids=["small", "large"])
+@pytest.mark.parametrize("seed", range(0, 40, 4))
+def test_random_explicit_collections_gpu(cuda, seed, dims):
+    """The same random collections through the kernel: gathers, ragged and full transposing sub-tiles,
+    1- to 16-byte units."""
+    from tests import gpu_util as G
+    src, dst, a, want = random_explicit_case(seed, dims)
+    print("seed", seed, "dims", dims[-1], "bytes", sum(n for _, n in dst), flush=True)
+    tpx.tpx_set_option("tile_bytes", 4096 if dims[-1] < 100 else 131072)
+    try:
+        plan = plan_of(src, dst)
+    finally:
+        tpx.tpx_set_option("tile_bytes", 131072)
+    got, _ = G.execute(plan, [torch.from_numpy(x).cuda() for x in a])
+    torch.cuda.synchronize()
+    for r in range(len(dst)):
+        assert np.array_equal(got[r].cpu().numpy(), want[r]), (seed, r)
 
 
 @pytest.mark.gpu

@@ -161,9 +161,10 @@ class Plan:
         self._h = _P(handle)
         self.dst_cursors = dst_cursors
 
-    def close(self) -> None:
+    def close(self, _free=_lib.tpx_free) -> None:
+        # _free is bound at definition time: at interpreter shutdown the module globals may be gone already
         if self._h:
-            _lib.tpx_free(self._h)
+            _free(self._h)
             self._h = None
 
     def __del__(self):

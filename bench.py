@@ -95,6 +95,8 @@ def main() -> int:
     ap.add_argument("--variant", type=int, default=-1)
     ap.add_argument("--streams", type=int, default=0)
     ap.add_argument("--no-probe", action="store_true")
+    ap.add_argument("--share-reads", action="store_true",
+                    help="plan with the share_reads option: replicas of a group are all written from one read")
     ap.add_argument("--fill", choices=["synth", "cheap"], default="synth",
                     help="source contents: seeded synthetic state, or one cheap fill per buffer (for profiler runs)")
     args = ap.parse_args()
@@ -119,6 +121,8 @@ def main() -> int:
         tpx.tpx_set_option("variant", args.variant)
     if args.streams:
         tpx.tpx_set_option("streams", args.streams)
+    if args.share_reads:
+        tpx.tpx_set_option("share_reads", 1)
 
     if args.workload == DATASET_WORKLOAD:
         return bench_dataset(args)
@@ -234,7 +238,8 @@ def main() -> int:
         "dtype": "u8", "data": "synthetic",
         "config": {"workload": args.workload, "state_bytes_read": stats["bytes_read"],
                    "state_bytes_written": stats["bytes_written"], "n_boxes": stats["n_boxes"],
-                   "n_tiles": stats["n_tiles"], "src_ranks": n_src, "dst_ranks": n_dst},
+                   "n_tiles": stats["n_tiles"], "src_ranks": n_src, "dst_ranks": n_dst,
+                   "share_reads": int(args.share_reads)},
         "pct_of_hbm_peak": round(100 * achieved / HBM_PEAK_GBPS, 2),
         "ms_per_reconfig": {"plan_host": round(plan_ms, 4), "kernel": round(kernel_ms_avg, 4),
                             "isolated_plan_upload_kernel": round(latency_ms, 4),

@@ -277,6 +277,10 @@ const char* tpx_last_error(void);
  *                 distant regions of the buffers
  *   "max_multicast"  most replicas one move may be written to (1 .. 128; default 8; 1 = every replica is
  *                 copied separately)
+ *   "share_reads" 0 (default): every destination rank reads from the holder section 6.5's locality rule
+ *                 picks for it (its own device first), which minimises bytes_cross_rank; 1: all ranks of a
+ *                 replica group read what the group's first rank reads, so a piece wanted by n replicas is
+ *                 read once and written n times - fewer bytes through memory when all buffers share one GPU
  * Errors: INVALID_ARG for an unknown key or a value out of range. */
 tpx_status tpx_set_option(const char* key, uint64_t value);
 

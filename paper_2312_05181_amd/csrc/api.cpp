@@ -248,6 +248,11 @@ tpx_status tpx_set_option(const char* key, uint64_t value) {
     tuning().variant = value;
     return TPX_OK;
   }
+  if (!std::strcmp(key, "share_reads")) {
+    if (value > 1) return fail(TPX_ERR_INVALID_ARG, "share_reads must be 0 or 1");
+    tuning().share_reads = value;
+    return TPX_OK;
+  }
   if (!std::strcmp(key, "max_multicast")) {
     if (value < 1 || value > 128) return fail(TPX_ERR_INVALID_ARG, "max_multicast must be in [1, 128]");
     tuning().max_multicast = value;

@@ -186,6 +186,10 @@ tpx_status plan_model_moves(tpx_plan_s& plan) {
         if (st) return st;
       }
     }
+    // With every buffer in one GPU's memory "the same device" saves nothing, while one shared source
+    // makes the whole group one multicast move: each piece is read once instead of once per distinct choice.
+    if (tuning().share_reads)
+      for (uint32_t dn = 1; dn < g.count; ++dn) choice[dn] = choice[0];
     // pass 2: one set of moves per run of consecutive members with identical choices
     for (uint32_t d0 = 0; d0 < g.count;) {
       uint32_t d1 = d0 + 1;

@@ -99,6 +99,7 @@ struct Tuning {
   uint64_t tile_bytes = 131072;
   uint64_t streams = 4;   // tile order: workgroup b works on contiguous part b % streams of the plan
   uint64_t max_multicast = 8;  // most destinations one move may be replicated to
+  uint64_t share_reads = 0;    // 1: all members of a replica group read what its first member reads
   uint64_t variant = 0;   // 0 = chosen from the tile size (1024 threads x 8 nontemporal loads for 128 KiB tiles)
 };
 Tuning& tuning();

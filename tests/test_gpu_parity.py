@@ -291,6 +291,18 @@ def test_multicast_small(cuda):
     _check_small(WIDE, synth.MIX_GPT, Parallel(2, 1, 2), Parallel(4, 1, 4))
 
 
+def test_shared_reads_eight_way_multicast(cuda):
+    """Option share_reads on data-parallel scale-out: one read feeds up to eight replicas."""
+    tpx.tpx_set_option("share_reads", 1)
+    try:
+        plan = _check_small(SMALL, SMALL_MIX, Parallel(1, 1, 4), Parallel(1, 1, 8))
+        assert all(b.n_dst == 8 for b in plan.boxes())
+        _check_small(WIDE, synth.MIX_GPT, Parallel(2, 1, 2), Parallel(2, 1, 12))
+        _check_small(ODD, ODD_MIX, Parallel(3, 1, 2), Parallel(4, 1, 5, w_transposed=1))
+    finally:
+        tpx.tpx_set_option("share_reads", 0)
+
+
 MID = Model(n_layers=2, hidden=512, n_heads=8, ffn=2048, vocab_true=4096, max_pos=64)
 
 

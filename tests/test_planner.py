@@ -197,6 +197,32 @@ def test_scale_out_writes_every_replica():
     assert s["bytes_cross_rank"] == 0 and s["bytes_read"] == s["bytes_written"]
 
 
+@pytest.mark.parametrize("src,dst", [(Parallel(1, 1, 4), Parallel(1, 1, 8)), (Parallel(2, 1, 2), Parallel(2, 1, 12)),
+                                     (Parallel(2, 2, 2), Parallel(4, 1, 3)), (Parallel(2, 1, 3), Parallel(2, 1, 2))])
+def test_share_reads_reads_every_piece_once(src, dst):
+    """Option share_reads: a replica group reads what its first member reads - same bytes land, each
+    distinct piece is read once per multicast move (at most max_multicast destinations each)."""
+    model, mix = SMALL, SMALL_MIX
+    src_bufs = H.np_bufs(H.make_src_bufs(model, src, 23, mix))
+    want = oreshard.reshard(model, src, dst, src_bufs)
+    local = plan_for(model, src, dst).stats()
+    tpx.tpx_set_option("share_reads", 1)
+    try:
+        plan = plan_for(model, src, dst)
+    finally:
+        tpx.tpx_set_option("share_reads", 0)
+    for how in (host_exec.run_boxes, host_exec.run_tiles):
+        got = [np.full(plan.buffer_bytes(1, r), H.POISON, dtype=np.uint8) for r in range(dst.n_ranks)]
+        how(plan, src_bufs, got)
+        assert all(np.array_equal(g, w) for g, w in zip(got, want))
+    s = plan.stats()
+    one_replica = oreshard.state_bytes(model, Parallel(dst.T, dst.P, 1))
+    assert s["bytes_written"] == local["bytes_written"] == dst.D * one_replica
+    assert s["bytes_read"] == -(-dst.D // 8) * one_replica <= local["bytes_read"]
+    assert s["bytes_cross_rank"] >= local["bytes_cross_rank"]      # the price: locality is given up
+    assert {b.n_dst for b in plan.boxes()} == ({8, dst.D % 8} - {0} if dst.D > 8 else {dst.D})
+
+
 def _identity_maps(model, par, mix):
     """Per rank: int64 array with a unique id (tensor, kind, position) per element slot of 2 bytes."""
     out = []

@@ -212,6 +212,41 @@ def test_full_size_workload(cuda, cfg):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("cfg", [2, 5])
+def test_full_size_round_trip_and_composition(cuda, cfg):
+    """Properties that hold at any size, in the launch configuration the benchmark times: A -> B -> A gives
+    back every tensor byte of A, and A -> B -> C lands the same bytes as A -> C (workload 5 grows the padded
+    vocabulary on the way out: the way back drops the zero rows again, and C, padded like B, gets the same
+    zero rows either way)."""
+    model, a, b, mix, seed = H.CONFIGS[cfg]
+    c = Parallel(1, 2, 1) if cfg == 2 else Parallel(6, 1, 1)
+    src_descs = H.manifest_descs(model, a)
+    src_gpu = []
+    for descs, n in src_descs:
+        buf = G.alloc(n, H.SRC_GAP)
+        synth.fill_buffer(buf, descs, seed, mix)
+        src_gpu.append(buf)
+    print("workload", cfg, "A->B", flush=True)
+    mid, _ = G.execute(plan_for(model, a, b), src_gpu)
+    print("workload", cfg, "B->A", flush=True)
+    back, _ = G.execute(plan_for(model, b, a), mid)
+    torch.cuda.synchronize()
+    for r, (descs, n) in enumerate(src_descs):
+        for d in descs:
+            assert torch.equal(back[r][d.offset:d.offset + d.nbytes], src_gpu[r][d.offset:d.offset + d.nbytes]), (r, d.tensor_id, d.kind)
+    del back
+    torch.cuda.empty_cache()
+    print("workload", cfg, "B->C and A->C", flush=True)
+    via, _ = G.execute(plan_for(model, b, c), mid)
+    direct, _ = G.execute(plan_for(model, a, c), src_gpu)
+    torch.cuda.synchronize()
+    for r in range(c.n_ranks):        # whole buffers: tensor bytes and the untouched poison in the gaps
+        assert torch.equal(via[r], direct[r]), r
+    assert H.closed_form_mismatches(direct, model, a, c, seed, mix) == 0
+    del via, direct, mid, src_gpu
+    torch.cuda.empty_cache()
+
+
 # ---------------------------------------------------------------------------------------------
 # dataset state
 # ---------------------------------------------------------------------------------------------

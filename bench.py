@@ -75,11 +75,13 @@ DEFAULT_WORKLOAD = "gpt6.7b_(8,1,1)->(1,8,1)"
 # HBM bytes per launch of the copy kernel, measured with rocprofv3 FETCH_SIZE / WRITE_SIZE passes scaled by a plain
 # copy of known size (the summaries under profiles/ give the raw counter values), or None where not measured.
 MEASURED_TRAFFIC = {
-    "gpt6.7b_(8,1,1)->(1,8,1)": 186355265353,
+    "gpt6.7b_(8,1,1)->(1,8,1)": 186359356682,
     "gpt1.3b_(4,2,1)->(2,4,1)": 36857000000,
     "gpt2.7b_(4,4,2)->(2,4,1)": 74272000000,
     "gpt_h3072_T3->T4_padded_vocab": 80869000000,
-    "gpt1.3b_(4,2,1)->(4,2,2)_dp": 55528000000,
+    "gpt1.3b_(4,2,1)->(4,2,2)_dp": 55526000000,
+    "bert-large_(1,1,4)->(1,1,8)": 60847000000,
+    "bert-large_(1,1,4)->(1,1,8)|share_reads": 42149670154,
     "gpt1.3b_(4,2,1)->(2,4,1)_transposed_dst": 36855000000,
 }
 
@@ -197,7 +199,7 @@ def main() -> int:
 
     achieved = state_bytes / (kernel_ms_avg * 1e-3) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC.get(args.workload),
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC.get(args.workload + ("|share_reads" if args.share_reads else "")),
                 "kernel": "tpx_execute_tiles", "kernel_ms_avg": round(kernel_ms_avg, 4),
                 "kernel_ms_min": round(min(kernel_ms), 4), "algorithmic_bytes_per_launch": state_bytes}
 

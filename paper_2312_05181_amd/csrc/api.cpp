@@ -50,7 +50,8 @@ tpx_status tpx_plan(const tpx_model* model, const tpx_parallel* src, const tpx_p
     p->model = *model;
     tpx_status st = build_side(*model, *src, p->side[0]);
     if (!st) st = build_side(*model, *dst, p->side[1]);
-    if (!st) st = index_side(p->side[1], true);
+    if (!st) st = index_subs(p->side[0]);
+    if (!st) st = find_groups(p->side[1]);
     if (!st) st = plan_model_moves(*p);
     if (!st) st = finish_plan(*p);
     if (st) return st;
@@ -93,8 +94,9 @@ tpx_status tpx_plan_ptc(const tpx_ptc* src, const tpx_ptc* dst, tpx_plan_t** out
     std::unique_ptr<tpx_plan_s> p(new tpx_plan_s());
     tpx_status st = side_from_ptc(src, p->side[0], "source");
     if (!st) st = side_from_ptc(dst, p->side[1], "destination");
-    if (!st) st = index_side(p->side[0], false);
-    if (!st) st = index_side(p->side[1], true);
+    if (!st) st = index_subs(p->side[0]);
+    if (!st) st = index_subs(p->side[1]);  // only for its checks: equal or disjoint sub-tensors, one shape per tensor
+    if (!st) st = find_groups(p->side[1]);
     if (!st) st = plan_model_moves(*p);
     if (!st) st = finish_plan(*p);
     if (st) return st;

@@ -203,7 +203,7 @@ tpx_status build_side(const tpx_model& m, const tpx_parallel& par, Side& out) {
         out.bytes[rank] = (off + kAlign - 1) / kAlign * kAlign;
       }
   }
-  return index_side(out, false);
+  return TPX_OK;
 }
 
 // Checks every entry of every manifest: shape, storage order, size, placement inside the rank buffer,
@@ -238,9 +238,9 @@ tpx_status check_entries(Side& side) {
   return TPX_OK;
 }
 
-// Builds the per-tensor index (which distinct boxes of a tensor exist, who holds each) and the replica
-// groups (ranks with identical manifests whose indices form an arithmetic progression).
-tpx_status index_side(Side& side, bool want_groups) {
+// Builds the per-tensor index of a side: which distinct boxes of a tensor exist and who holds each.
+// Rejects sub-tensors of one tensor that disagree about its shape or overlap without being equal.
+tpx_status index_subs(Side& side) {
   side.key_of.clear();
   side.dense_key.clear();
   side.subs.clear();
@@ -288,9 +288,13 @@ tpx_status index_side(Side& side, bool want_groups) {
     std::sort(subs.begin(), subs.end(), [](const SubTensor& a, const SubTensor& b) {
       return std::lexicographical_compare(a.lo, a.lo + 4, b.lo, b.lo + 4);
     });
-  // replica groups
+  return TPX_OK;
+}
+
+// Partitions the ranks into replica groups: ranks with identical manifests whose indices form an
+// arithmetic progression.
+tpx_status find_groups(Side& side) {
   side.groups.clear();
-  if (!want_groups) return TPX_OK;
   std::vector<char> done(side.ranks.size(), 0);
   auto same_manifest = [&](uint32_t a, uint32_t b) {
     if (side.bytes[a] != side.bytes[b] || side.ranks[a].size() != side.ranks[b].size()) return false;

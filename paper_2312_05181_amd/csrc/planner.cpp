@@ -159,63 +159,89 @@ tpx_status plan_model_moves(tpx_plan_s& plan) {
   const Side& Sn = plan.side[1];
   plan.boxes.clear();
   uint64_t n_pieces = 0;
+  struct Piece {
+    uint64_t lo[4], hi[4];
+    const SubTensor* sub;  // nullptr: rows that exist only as new padding
+    const tpx_entry* sn;
+  };
+  std::vector<Piece> pieces;
+  std::vector<std::vector<int>> choice;
+  auto unrecoverable = [&](const tpx_entry& sn) {
+    return fail(TPX_ERR_UNRECOVERABLE, "no surviving holder of a piece of tensor " + std::to_string(sn.tensor_id) +
+                                           (sn.name < N_NAMES && S.tp_degree ? std::string(" (") + param_name(sn.name) + ", layer " + std::to_string(sn.layer) + ")" : std::string()));
+  };
+  auto emit = [&](const Piece& pc, int h, uint32_t rn, uint32_t n_dst, uint32_t stride) {
+    tpx_box b;
+    if (!pc.sub) {
+      b = lower_piece(pc.lo, pc.hi, nullptr, 0, *pc.sn, rn);
+    } else {
+      const Holder& who = pc.sub->holders[size_t(h)];
+      b = lower_piece(pc.lo, pc.hi, &S.ranks[who.rank][who.entry], who.rank, *pc.sn, rn);  // move(w, r_w, r')
+    }
+    b.n_dst = n_dst;
+    b.dst_rank_stride = n_dst > 1 ? stride : 0;
+    plan.boxes.push_back(b);
+  };
   // RE-PARTITION: foreach r' in R', foreach sub-tensor s' allocated to r'.  Ranks of a replica group hold
   // identical sub-collections at identical offsets; members that also make the same source choices are
   // served by one multicast move (read once, written to each), so a group is planned together.
   for (const ReplicaGroup& g : Sn.groups) {
     const uint32_t r0 = g.first;
-    // pass 1: every member's source choice for every piece (get_resource)
-    std::vector<std::vector<int>> choice(g.count);
+    // SPLIT, once per group: the pieces of every sub-tensor of the (shared) manifest
+    pieces.clear();
+    for (const tpx_entry& sn : Sn.ranks[r0]) {
+      const int32_t key = S.find_key(sn.tensor_id, sn.kind);  // get_base_tensor: the same tensor, old side
+      if (key < 0) return fail(TPX_ERR_INVALID_ARG, "tensor " + std::to_string(sn.tensor_id) + " is missing from the source configuration");
+      const auto& subs = S.subs[size_t(key)];
+      const tpx_entry& any = S.ranks[subs[0].holders[0].rank][subs[0].holders[0].entry];
+      tpx_status st = for_each_piece(sn, any, subs, [&](const uint64_t* lo, const uint64_t* hi, const SubTensor* sub) -> tpx_status {
+        Piece pc;
+        for (uint32_t k = 0; k < 4; ++k) { pc.lo[k] = lo[k]; pc.hi[k] = hi[k]; }
+        pc.sub = sub;
+        pc.sn = &sn;
+        pieces.push_back(pc);
+        return TPX_OK;
+      });
+      if (st) return st;
+      // merge(W): implicit - the pieces are addressed inside s' itself
+    }
+    if (g.count == 1) {  // no replicas: choose (get_resource) and move in one go
+      for (const Piece& pc : pieces) {
+        int h = -1;
+        if (pc.sub) {
+          h = get_resource(S, Sn, *pc.sub, r0);
+          if (h < 0) return unrecoverable(*pc.sn);
+          ++n_pieces;
+        }
+        emit(pc, h, r0, 1, 0);
+      }
+      continue;
+    }
+    // every member's source choice for every piece
+    choice.assign(g.count, std::vector<int>());
     for (uint32_t dn = 0; dn < g.count; ++dn) {
       const uint32_t rn = r0 + dn * g.stride;
-      for (const tpx_entry& sn : Sn.ranks[r0]) {
-        const int32_t key = S.find_key(sn.tensor_id, sn.kind);  // get_base_tensor: the same tensor, old side
-        if (key < 0) return fail(TPX_ERR_INVALID_ARG, "tensor " + std::to_string(sn.tensor_id) + " is missing from the source configuration");
-        const auto& subs = S.subs[size_t(key)];
-        const tpx_entry& any = S.ranks[subs[0].holders[0].rank][subs[0].holders[0].entry];
-        tpx_status st = for_each_piece(sn, any, subs, [&](const uint64_t*, const uint64_t*, const SubTensor* sub) -> tpx_status {
-          if (!sub) { choice[dn].push_back(-1); return TPX_OK; }
-          const int h = get_resource(S, Sn, *sub, rn);
-          if (h < 0)
-            return fail(TPX_ERR_UNRECOVERABLE, "no surviving holder of a piece of tensor " + std::to_string(sn.tensor_id) +
-                                                   (sn.name < N_NAMES && S.tp_degree ? std::string(" (") + param_name(sn.name) + ", layer " + std::to_string(sn.layer) + ")" : std::string()));
-          choice[dn].push_back(h);
+      choice[dn].reserve(pieces.size());
+      for (const Piece& pc : pieces) {
+        int h = -1;
+        if (pc.sub) {
+          h = get_resource(S, Sn, *pc.sub, rn);
+          if (h < 0) return unrecoverable(*pc.sn);
           ++n_pieces;
-          return TPX_OK;
-        });
-        if (st) return st;
+        }
+        choice[dn].push_back(h);
       }
     }
     // With every buffer in one GPU's memory "the same device" saves nothing, while one shared source
     // makes the whole group one multicast move: each piece is read once instead of once per distinct choice.
     if (tuning().share_reads)
       for (uint32_t dn = 1; dn < g.count; ++dn) choice[dn] = choice[0];
-    // pass 2: one set of moves per run of consecutive members with identical choices
+    // one set of moves per run of consecutive members with identical choices
     for (uint32_t d0 = 0; d0 < g.count;) {
       uint32_t d1 = d0 + 1;
       while (d1 < g.count && d1 - d0 < tuning().max_multicast && choice[d1] == choice[d0]) ++d1;
       const uint32_t rn = r0 + d0 * g.stride;
-      size_t cursor = 0;
-      for (const tpx_entry& sn : Sn.ranks[rn]) {
-        const auto& subs = S.subs[size_t(S.find_key(sn.tensor_id, sn.kind))];
-        const tpx_entry& any = S.ranks[subs[0].holders[0].rank][subs[0].holders[0].entry];
-        tpx_status st = for_each_piece(sn, any, subs, [&](const uint64_t* lo, const uint64_t* hi, const SubTensor* sub) -> tpx_status {
-          const int h = choice[d0][cursor++];
-          tpx_box b;
-          if (!sub) {
-            b = lower_piece(lo, hi, nullptr, 0, sn, rn);
-          } else {
-            const Holder& who = sub->holders[size_t(h)];
-            b = lower_piece(lo, hi, &S.ranks[who.rank][who.entry], who.rank, sn, rn);  // move(w, r_w, r')
-          }
-          b.n_dst = d1 - d0;
-          b.dst_rank_stride = b.n_dst > 1 ? g.stride : 0;
-          plan.boxes.push_back(b);
-          return TPX_OK;
-        });
-        if (st) return st;
-        // merge(W): implicit - the pieces were addressed inside s' itself
-      }
+      for (size_t i = 0; i < pieces.size(); ++i) emit(pieces[i], choice[d0][i], rn, d1 - d0, g.stride);
       d0 = d1;
     }
   }

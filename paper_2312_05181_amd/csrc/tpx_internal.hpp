@@ -64,7 +64,7 @@ struct Side {
   std::vector<uint8_t> alive;                 // per rank
   std::vector<std::vector<tpx_entry>> ranks;  // manifest of every rank buffer
   std::vector<uint64_t> bytes;                // size of every rank buffer
-  // index, built by index_side(): state tensor (tensor_id, kind) -> dense key -> its distinct sub-tensors,
+  // index, built by index_subs(): state tensor (tensor_id, kind) -> dense key -> its distinct sub-tensors,
   // sorted by position
   std::unordered_map<uint64_t, uint32_t> key_of;   // used when the ids are too sparse for the dense table
   std::vector<int32_t> dense_key;                  // [tensor_id * n_kinds + kind] -> key, -1 = absent
@@ -82,7 +82,8 @@ struct Side {
   std::vector<ReplicaGroup> groups;           // partition of the ranks into replica groups
 };
 tpx_status check_entries(Side& side);  // validates every manifest entry, fills nbytes
-tpx_status index_side(Side& side, bool want_groups);  // builds key_of, subs (and groups) from ranks
+tpx_status index_subs(Side& side);    // builds key_of / dense_key and subs from ranks (needed on the source side)
+tpx_status find_groups(Side& side);   // builds groups from ranks (needed on the destination side)
 
 // Error reporting: sets the thread-local message and returns `st`.
 tpx_status fail(tpx_status st, const std::string& msg);

@@ -11,7 +11,9 @@ parallelizable tensor collection PTC = (T, sigma, phi, alpha):
   * sigma  slicing (tensor parallelism): which axis of a tensor is cut into
            `T` equal parts, or none (replicated on every tensor-parallel rank);
   * phi    partitioning: a layer's tensors belong to the pipeline stage that
-           owns the layer; every data-parallel replica holds a full copy;
+           owns the layer; every data-parallel replica holds a full copy, except
+           for state kinds marked as sharded over the replicas (sharded data
+           parallelism: replica d keeps the d-th chunk of each of its tensors);
   * alpha  allocation: sub-collection (t, p, d) lives in rank buffer
            t + T*(d + D*p).
 The paper leaves sigma/phi/alpha to the parallelizer (section 5.1: a JSON
@@ -79,6 +81,7 @@ class Parallel:
     stage_first_layer: Optional[tuple] = None   # P+1 ascending boundaries; None = even split
     qkv_layout: int = 0                         # 0 head-major [a,3,d,*]; 1 qkv-major [3,a,d,*]
     w_transposed: int = 0                       # 1: 2-D weights stored [in, out] instead of [out, in]
+    shard_kinds: int = 0                        # bit k set: state kind k is sharded over the D replicas
 
     @property
     def n_ranks(self) -> int:
@@ -123,6 +126,8 @@ def check(model: Model, par: Parallel) -> None:
         raise ValueError("heads / ffn / hidden not divisible by T")
     vocab_padded(model, par.T)
     stage_bounds(model, par)
+    if par.shard_kinds >> len(model.state_elem_bytes):
+        raise ValueError("shard_kinds names a state kind the model does not have")
 
 
 def stage_bounds(model: Model, par: Parallel) -> tuple:
@@ -198,6 +203,21 @@ def shard_range(full_shape: Sequence[int], axis, T: int, t: int):
     return tuple(lo), tuple(hi)
 
 
+def replica_range(lo, hi, perm, D: int, d: int):
+    """Sharded data parallelism: of the block [lo, hi) that a (t, p) share holds, replica d keeps chunk d
+    along the block's outermost stored axis (perm[0]), chunks of ceil(extent / D) - the last ones may be
+    short or empty.  Returns (lo, hi) of the chunk, or None if it is empty."""
+    ax = perm[0]
+    n = hi[ax] - lo[ax]
+    c = -(-n // D)
+    a, b = min(n, d * c), min(n, (d + 1) * c)
+    if a == b:
+        return None
+    lo2, hi2 = list(lo), list(hi)
+    lo2[ax], hi2[ax] = lo[ax] + a, lo[ax] + b
+    return tuple(lo2), tuple(hi2)
+
+
 def _numel(lo, hi) -> int:
     n = 1
     for l, u in zip(lo, hi):
@@ -209,13 +229,18 @@ def rank_manifest(model: Model, par: Parallel, rank: int):
     """(entries, buffer_bytes) of one rank buffer: state-kind-major arenas, inside
     each the stage's tensors in packing order, each aligned to ALIGN bytes."""
     check(model, par)
-    t, p, _d = coords_of(par, rank)
+    t, p, d = coords_of(par, rank)
     entries = []
     off = 0
     for kind, eb in enumerate(model.state_elem_bytes):
         for name, layer in stage_tensors(model, par, p):
             full, axis, perm = canonical(model, par, name)
             lo, hi = shard_range(full, axis, par.T, t)
+            if (par.shard_kinds >> kind) & 1:
+                chunk = replica_range(lo, hi, perm, par.D, d)
+                if chunk is None:
+                    continue            # this replica holds nothing of the tensor
+                lo, hi = chunk
             off = -(-off // ALIGN) * ALIGN
             entries.append(Entry(tensor_id(name, layer), kind, eb, off, full, lo, hi, perm, name, layer))
             off += _numel(lo, hi) * eb

@@ -149,6 +149,51 @@ def test_shards_are_numpy_split_of_full(T):
             assert np.array_equal(got, want), (rank, spec.NAMES[e.name][0])
 
 
+@pytest.mark.parametrize("D", [2, 3, 4, 7])
+@pytest.mark.parametrize("tags", [dict(), dict(qkv_layout=1), dict(w_transposed=1)])
+def test_sharded_kinds_partition_each_share(D, tags):
+    """Sharded data parallelism: the chunks the D replicas keep of a tensor, concatenated in replica order
+    along the outermost stored axis, are exactly the block a replica of the unsharded configuration holds;
+    chunk d has min(c, max(0, n - d*c)) rows with c = ceil(n / D); kinds that are not sharded are untouched."""
+    model, mix, seed = SMALL, SMALL_MIX, 13
+    whole, cut = Parallel(2, 2, 1, **tags), Parallel(2, 2, D, shard_kinds=2, **tags)
+    ref = H.np_bufs(H.make_src_bufs(model, whole, seed, mix))
+    got = H.np_bufs(H.make_src_bufs(model, cut, seed, mix))
+    total = 0
+    for t in range(2):
+        for p in range(2):
+            for e in spec.rank_manifest(model, whole, spec.rank_of(whole, t, p, 0))[0]:
+                stored = tuple(e.hi[a] - e.lo[a] for a in e.perm)
+                want = ref[spec.rank_of(whole, t, p, 0)][e.offset:e.offset + int(np.prod(stored)) * e.elem_bytes]
+                chunks = []
+                for d in range(D):
+                    r = spec.rank_of(cut, t, p, d)
+                    mine = [x for x in spec.rank_manifest(model, cut, r)[0] if (x.tensor_id, x.kind) == (e.tensor_id, e.kind)]
+                    if e.kind == 0:                    # replicated as before
+                        assert len(mine) == 1 and (mine[0].lo, mine[0].hi) == (e.lo, e.hi)
+                        x = mine[0]
+                        assert np.array_equal(got[r][x.offset:x.offset + want.nbytes], want)
+                        continue
+                    n = stored[0]
+                    c = -(-n // D)
+                    rows = min(c, max(0, n - d * c))
+                    assert len(mine) == (1 if rows else 0), (d, n)
+                    if rows:
+                        x = mine[0]
+                        assert x.hi[x.perm[0]] - x.lo[x.perm[0]] == rows
+                        nbytes = rows * int(np.prod(stored[1:])) * x.elem_bytes
+                        chunks.append(got[r][x.offset:x.offset + nbytes])
+                        total += nbytes
+                if e.kind == 1:
+                    assert np.array_equal(np.concatenate(chunks), want), (t, p, spec.NAMES[e.name][0])
+    # closed form: the sharded kind is stored once, not D times
+    one = Parallel(2, 2, 1)
+    per_kind = [sum(int(np.prod([h - l for l, h in zip(e.lo, e.hi)])) * e.elem_bytes
+                    for r in range(one.n_ranks) for e in spec.rank_manifest(model, one, r)[0] if e.kind == k) for k in (0, 1)]
+    assert total == per_kind[1]
+    assert oreshard.state_bytes(model, cut) == D * per_kind[0] + per_kind[1]
+
+
 # --------------------------------------------------------------------------
 # mathematics: a tensor-parallel layer built from the shards computes the same
 # function as the unsharded layer
@@ -267,6 +312,11 @@ PAIRS = [
     (Parallel(2, 2, 1), Parallel(2, 2, 2)),
     (Parallel(2, 1, 1, qkv_layout=1), Parallel(3, 2, 1)),
     (Parallel(2, 1, 1), Parallel(4, 1, 1, qkv_layout=1, w_transposed=1)),
+    # state kinds sharded over the data-parallel replicas (bit k of shard_kinds)
+    (Parallel(2, 1, 2, shard_kinds=2), Parallel(2, 1, 4, shard_kinds=2)),
+    (Parallel(4, 2, 2, shard_kinds=2), Parallel(2, 2, 1)),
+    (Parallel(2, 1, 1), Parallel(3, 2, 3, shard_kinds=3)),
+    (Parallel(2, 1, 3, shard_kinds=1, qkv_layout=1), Parallel(1, 2, 5, shard_kinds=2, w_transposed=1)),
 ]
 
 
@@ -392,6 +442,27 @@ def test_pins_catch_a_plain_row_split_of_qkv_major(monkeypatch):
     monkeypatch.setattr(spec, "canonical", wrong)
     with pytest.raises((AssertionError, ValueError, IndexError)):
         test_tensor_parallel_forward_equivalence(Parallel(3, 1, 1, qkv_layout=1, w_transposed=0))
+
+
+def test_pins_catch_floor_sized_replica_chunks(monkeypatch):
+    """Planted mistake: chunks of floor(n / D) rows leave the tail of a sharded tensor with no holder."""
+    real = spec.replica_range
+
+    def wrong(lo, hi, perm, D, d):
+        ax = perm[0]
+        n = hi[ax] - lo[ax]
+        c = max(1, n // D)
+        a, b = min(n, d * c), min(n, (d + 1) * c)
+        if a == b:
+            return None
+        lo2, hi2 = list(lo), list(hi)
+        lo2[ax], hi2[ax] = lo[ax] + a, lo[ax] + b
+        return tuple(lo2), tuple(hi2)
+    monkeypatch.setattr(spec, "replica_range", wrong)
+    with pytest.raises(AssertionError):
+        test_sharded_kinds_partition_each_share(7, dict())
+    monkeypatch.setattr(spec, "replica_range", real)
+    test_sharded_kinds_partition_each_share(7, dict())
 
 
 def test_pins_catch_a_dropped_paste(monkeypatch):

@@ -68,6 +68,12 @@ LAYOUT_PAIRS = {
     "gpt1.3b_(4,2,1)->(4,2,1)_transposed_dst": (_G13, _c(4, 2, 1), _c(4, 2, 1, w_transposed=1), "gpt", 23),
 }
 WORKLOADS.update(LAYOUT_PAIRS)
+# sharded data parallelism: the fp32 optimizer state (kinds 1-3) is cut between the D replicas instead of copied
+SHARDED_PAIRS = {
+    "gpt2.7b_(2,2,4)->(4,2,2)_sharded_opt": (_G27, _c(2, 2, 4, shard_kinds=14), _c(4, 2, 2, shard_kinds=14), "gpt", 31),
+    "gpt1.3b_(4,1,4)->(2,2,2)_sharded_opt": (_G13, _c(4, 1, 4, shard_kinds=14), _c(2, 2, 2, shard_kinds=14), "gpt", 32),
+}
+WORKLOADS.update(SHARDED_PAIRS)
 DATASET_WORKLOAD = "dataset_1e8_D6->D4"
 DATASET_CFG = dict(n_samples=10 ** 8, global_batch=768, D_src=6, D_dst=4, steps_done=65000, seed=6)
 DEFAULT_WORKLOAD = "gpt6.7b_(8,1,1)->(1,8,1)"
@@ -358,8 +364,10 @@ def cpu_baseline(args, model, src, dst, plan, src_bufs, dst_bufs, src_ptrs, dst_
 
     om = spec.Model(model["n_layers"], model["hidden"], model["n_heads"], model["ffn"], model["vocab_true"],
                     model.get("max_pos", 1024), model.get("vocab_divisor", 0), tuple(model["state_elem_bytes"]))
-    osrc = spec.Parallel(src["T"], src["P"], src["D"], src.get("stage_first_layer"))
-    odst = spec.Parallel(dst["T"], dst["P"], dst["D"], dst.get("stage_first_layer"))
+    def opar(c):
+        return spec.Parallel(c["T"], c["P"], c["D"], c.get("stage_first_layer"), c.get("qkv_layout", 0),
+                             c.get("w_transposed", 0), c.get("shard_kinds", 0))
+    osrc, odst = opar(src), opar(dst)
     src_lay, dst_lay = oreshard.Layout(om, osrc), oreshard.Layout(om, odst)
     layers = min(args.cpu_layers, om.n_layers)
     work = [(4 + l * 12 + k, kind) for l in range(layers) for k in range(12) for kind in range(len(om.state_elem_bytes))]

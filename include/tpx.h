@@ -70,6 +70,11 @@ typedef struct {
   uint32_t w_transposed;             /* 1: 2-D weights are stored [in, out] instead of [out, in] */
   const uint8_t* rank_alive;         /* T*P*D bytes, 0 = this rank's buffer is lost (section 5.3); NULL = all alive.
                                         Only meaningful for the source configuration. */
+  uint32_t shard_kinds;              /* phi, sharded data parallelism: bit k set = state kind k is not replicated over
+                                        the D replicas but cut between them: of each block its (t, p) share holds,
+                                        replica d stores chunk d of ceil(n / D) rows along the block's outermost
+                                        stored axis (n its extent there); short or empty chunks at the end; a
+                                        replica with an empty chunk has no entry for the tensor.  0 = none. */
 } tpx_parallel;
 
 /* One stored sub-tensor of a rank buffer ("/<rank>/<module path>/<param>", section 5.2).

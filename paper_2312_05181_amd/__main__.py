@@ -15,9 +15,9 @@ from . import binding as B
 from . import tpx_param_name, tpx_plan
 
 
-def _cfg(text: str, stages, qkv, transposed) -> dict:
+def _cfg(text: str, stages, qkv, transposed, shard_kinds) -> dict:
     t, p, d = (int(x) for x in text.split(","))
-    out = dict(T=t, P=p, D=d, qkv_layout=qkv, w_transposed=transposed)
+    out = dict(T=t, P=p, D=d, qkv_layout=qkv, w_transposed=transposed, shard_kinds=shard_kinds)
     if stages:
         out["stage_first_layer"] = tuple(int(x) for x in stages.split(","))
     return out
@@ -43,6 +43,8 @@ def main(argv=None) -> int:
     ap.add_argument("--dst-qkv", type=int, default=0)
     ap.add_argument("--src-transposed", type=int, default=0)
     ap.add_argument("--dst-transposed", type=int, default=0)
+    ap.add_argument("--src-shard-kinds", type=int, default=0, help="bit k: state kind k is sharded over the D replicas")
+    ap.add_argument("--dst-shard-kinds", type=int, default=0)
     ap.add_argument("--side", choices=["src", "dst"], default="dst")
     ap.add_argument("--rank", type=int, default=0)
     a = ap.parse_args(argv)
@@ -50,8 +52,8 @@ def main(argv=None) -> int:
                  vocab_divisor=a.vocab_divisor, state_elem_bytes=tuple(int(x) for x in a.state_bytes.split(",")),
                  tied_head=a.tied_head)
     try:
-        plan = tpx_plan(model, _cfg(a.src, a.src_stages, a.src_qkv, a.src_transposed),
-                        _cfg(a.dst, a.dst_stages, a.dst_qkv, a.dst_transposed))
+        plan = tpx_plan(model, _cfg(a.src, a.src_stages, a.src_qkv, a.src_transposed, a.src_shard_kinds),
+                        _cfg(a.dst, a.dst_stages, a.dst_qkv, a.dst_transposed, a.dst_shard_kinds))
     except B.TpxError as e:
         print(str(e), file=sys.stderr)
         return 1

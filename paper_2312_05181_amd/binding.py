@@ -46,7 +46,7 @@ class tpx_model(C.Structure):
 class tpx_parallel(C.Structure):
     _fields_ = [("T", C.c_uint32), ("P", C.c_uint32), ("D", C.c_uint32),
                 ("stage_first_layer", C.POINTER(C.c_uint32)), ("qkv_layout", C.c_uint32),
-                ("w_transposed", C.c_uint32), ("rank_alive", C.POINTER(C.c_uint8))]
+                ("w_transposed", C.c_uint32), ("rank_alive", C.POINTER(C.c_uint8)), ("shard_kinds", C.c_uint32)]
 
 
 class tpx_entry(C.Structure):
@@ -139,14 +139,14 @@ def _model_struct(n_layers, hidden, n_heads, ffn, vocab_true, max_pos=1024, voca
     return m
 
 
-def _parallel_struct(T, P, D, stage_first_layer=None, qkv_layout=0, w_transposed=0, rank_alive=None):
+def _parallel_struct(T, P, D, stage_first_layer=None, qkv_layout=0, w_transposed=0, rank_alive=None, shard_kinds=0):
     keep = []
     p = tpx_parallel(T, P, D)
     if stage_first_layer is not None:
         arr = (C.c_uint32 * len(stage_first_layer))(*stage_first_layer)
         keep.append(arr)
         p.stage_first_layer = C.cast(arr, C.POINTER(C.c_uint32))
-    p.qkv_layout, p.w_transposed = qkv_layout, w_transposed
+    p.qkv_layout, p.w_transposed, p.shard_kinds = qkv_layout, w_transposed, shard_kinds
     if rank_alive is not None:
         arr = (C.c_uint8 * len(rank_alive))(*[1 if a else 0 for a in rank_alive])
         keep.append(arr)
@@ -240,7 +240,7 @@ class Plan:
 
 def tpx_plan(model: dict, src: dict, dst: dict) -> Plan:
     """model: kwargs of the GPT-style model; src / dst: kwargs T, P, D[, stage_first_layer, qkv_layout,
-    w_transposed, rank_alive]."""
+    w_transposed, rank_alive, shard_kinds]."""
     m = _model_struct(**model)
     s, keep_s = _parallel_struct(**src)
     d, keep_d = _parallel_struct(**dst)

@@ -128,6 +128,7 @@ tpx_status build_side(const tpx_model& m, const tpx_parallel& par, Side& out) {
   const uint64_t n_ranks = uint64_t(par.T) * par.P * par.D;
   if (n_ranks > TPX_MAX_RANKS) return fail(TPX_ERR_INVALID_ARG, "more than TPX_MAX_RANKS ranks in one configuration");
   if (par.qkv_layout > 1 || par.w_transposed > 1) return fail(TPX_ERR_INVALID_ARG, "unknown layout tag");
+  if (par.shard_kinds >> m.n_state_kinds) return fail(TPX_ERR_INVALID_ARG, "shard_kinds names a state kind the model does not have");
   if (m.n_heads % par.T || m.ffn % par.T || m.hidden % par.T)
     return fail(TPX_ERR_INDIVISIBLE, "heads, ffn or hidden not divisible by T");
   out = Side{};
@@ -171,7 +172,8 @@ tpx_status build_side(const tpx_model& m, const tpx_parallel& par, Side& out) {
         auto& man = out.ranks[rank];
         man.reserve(held.size() * m.n_state_kinds);
         uint64_t off = 0;
-        for (uint32_t k = 0; k < m.n_state_kinds; ++k)  // one arena per state kind
+        for (uint32_t k = 0; k < m.n_state_kinds; ++k) {  // one arena per state kind
+          const bool cut_over_d = (par.shard_kinds >> k) & 1;
           for (auto [name, layer] : held) {
             const Sigma& s = sig[name];
             tpx_entry e{};
@@ -192,14 +194,23 @@ tpx_status build_side(const tpx_model& m, const tpx_parallel& par, Side& out) {
                 e.lo[ax] = part * t;
                 e.hi[ax] = part * (t + 1);
               }
-              numel *= e.hi[ax] - e.lo[ax];
             }
+            if (cut_over_d) {  // replica d keeps chunk d along the outermost stored axis
+              const uint32_t ax = s.perm[0];
+              const uint64_t n = e.hi[ax] - e.lo[ax], c = (n + par.D - 1) / par.D;
+              const uint64_t a = std::min<uint64_t>(n, uint64_t(d) * c), b = std::min<uint64_t>(n, uint64_t(d + 1) * c);
+              if (a == b) continue;  // nothing of this tensor on this replica
+              e.hi[ax] = e.lo[ax] + b;
+              e.lo[ax] += a;
+            }
+            for (uint32_t ax = 0; ax < s.ndim; ++ax) numel *= e.hi[ax] - e.lo[ax];
             off = (off + kAlign - 1) / kAlign * kAlign;
             e.offset = off;
             e.nbytes = numel * e.elem_bytes;
             off += e.nbytes;
             man.push_back(e);
           }
+        }
         out.bytes[rank] = (off + kAlign - 1) / kAlign * kAlign;
       }
   }

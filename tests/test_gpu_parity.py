@@ -283,7 +283,8 @@ def test_dataset_full_size(cuda):
 # ---------------------------------------------------------------------------------------------
 def _paper_pairs():
     import bench
-    return [k for k in bench.PAPER_PAIRS if not k.startswith("gpt6.7b") and not k.startswith("gpt2.7b_(4,2,1)->(4,4")]
+    return [k for k in bench.PAPER_PAIRS if not k.startswith("gpt6.7b") and not k.startswith("gpt2.7b_(4,2,1)->(4,4")] + \
+        list(bench.SHARDED_PAIRS)          # plus the sharded-optimizer-state reshards, checked the same way
 
 
 @pytest.mark.parametrize("name", _paper_pairs())
@@ -292,12 +293,12 @@ def test_paper_reconfiguration_pairs(cuda, name):
     paper's evaluation: every destination tensor equals its closed-form contents, gaps stay untouched, and
     replicated destinations are written from a single read (multicast moves)."""
     import bench
-    mk_, s_, d_, _, seed = bench.PAPER_PAIRS[name]
+    mk_, s_, d_, _, seed = bench.WORKLOADS[name]
     print("pair", name, flush=True)
     model = Model(mk_["n_layers"], mk_["hidden"], mk_["n_heads"], mk_["ffn"], mk_["vocab_true"], mk_.get("max_pos", 1024),
                   mk_.get("vocab_divisor", 0), tuple(mk_["state_elem_bytes"]))
-    src = Parallel(s_["T"], s_["P"], s_["D"], s_.get("stage_first_layer"))
-    dst = Parallel(d_["T"], d_["P"], d_["D"], d_.get("stage_first_layer"))
+    src = Parallel(s_["T"], s_["P"], s_["D"], s_.get("stage_first_layer"), shard_kinds=s_.get("shard_kinds", 0))
+    dst = Parallel(d_["T"], d_["P"], d_["D"], d_.get("stage_first_layer"), shard_kinds=d_.get("shard_kinds", 0))
     mix = synth.MIX_GPT
     plan = plan_for(model, src, dst)
     st = plan.stats()

@@ -26,7 +26,7 @@ def mk(model: Model) -> dict:
 
 def pk(par: Parallel, **extra) -> dict:
     d = dict(T=par.T, P=par.P, D=par.D, stage_first_layer=par.stage_first_layer, qkv_layout=par.qkv_layout,
-             w_transposed=par.w_transposed)
+             w_transposed=par.w_transposed, shard_kinds=par.shard_kinds)
     d.update(extra)
     return d
 
@@ -47,9 +47,14 @@ def test_library_exports_every_declared_symbol():
     assert declared == set(tpx.EXPORTS)
 
 
-@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
-def test_manifest_equals_oracle_layout(cfg):
-    model, src, dst, _, _ = H.CONFIGS[cfg]
+def _layout_cases():
+    yield from ((H.CONFIGS[c][0], H.CONFIGS[c][1], H.CONFIGS[c][2]) for c in (1, 2, 3, 4, 5))
+    yield H.GPT_1_3B, Parallel(4, 2, 2, shard_kinds=14), Parallel(2, 2, 4, shard_kinds=14, qkv_layout=1)   # sharded optimizer state
+    yield H.TINY, Parallel(2, 1, 3, shard_kinds=7), Parallel(4, 2, 5, shard_kinds=2, w_transposed=1)
+
+
+@pytest.mark.parametrize("model,src,dst", list(_layout_cases()))
+def test_manifest_equals_oracle_layout(model, src, dst):
     plan = plan_for(model, src, dst)
     for side, par in ((0, src), (1, dst)):
         assert plan.num_buffers(side) == par.n_ranks
@@ -90,6 +95,13 @@ PAIRS = [
     (ODD, ODD_MIX, Parallel(3, 1, 1), Parallel(4, 2, 1, w_transposed=1)),
     (WIDE, H.synth.MIX_GPT, Parallel(2, 2, 1), Parallel(4, 1, 2)),
     (WIDE, H.synth.MIX_GPT, Parallel(8, 1, 1), Parallel(1, 2, 1)),
+    # state kinds sharded over the data-parallel replicas
+    (SMALL, SMALL_MIX, Parallel(2, 1, 2, shard_kinds=2), Parallel(2, 1, 4, shard_kinds=2)),
+    (SMALL, SMALL_MIX, Parallel(4, 2, 2, shard_kinds=2), Parallel(2, 2, 1)),
+    (SMALL, SMALL_MIX, Parallel(2, 1, 1), Parallel(3, 2, 3, shard_kinds=3)),
+    (SMALL, SMALL_MIX, Parallel(2, 1, 3, shard_kinds=1, qkv_layout=1), Parallel(1, 2, 5, shard_kinds=2, w_transposed=1)),
+    (ODD, ODD_MIX, Parallel(3, 1, 2, shard_kinds=2), Parallel(4, 1, 3, shard_kinds=3)),
+    (WIDE, H.synth.MIX_GPT, Parallel(2, 2, 2, shard_kinds=14), Parallel(4, 1, 4, shard_kinds=14)),
 ]
 
 
@@ -119,7 +131,7 @@ def test_plan_interpreted_on_cpu_matches_oracle(model, mix, src, dst, how):
         assert np.array_equal(cover[r], expect_cover), r
     s = plan.stats()
     assert s["bytes_written"] == oreshard.state_bytes(model, dst)
-    if dst.D == 1:
+    if dst.D == 1 or dst.shard_kinds == (1 << len(model.state_elem_bytes)) - 1:
         assert s["bytes_read"] == s["bytes_written"] - s["bytes_fill"]
     else:       # replicas fed by one multicast move read their source once
         assert s["bytes_read"] <= s["bytes_written"] - s["bytes_fill"]
@@ -282,6 +294,22 @@ def test_unrecoverable_when_no_holder_survives():
     with pytest.raises(tpx.TpxError) as ei:
         plan_for(SMALL, src, Parallel(1, 1, 1), rank_alive=alive)
     assert ei.value.status == B.TPX_ERR_UNRECOVERABLE
+
+
+def test_sharded_kinds_have_no_replica_to_recover_from():
+    """A state kind cut over the replicas is stored once: losing one rank loses its chunk, while the kinds
+    that are still replicated survive the same loss."""
+    src = Parallel(2, 1, 2, shard_kinds=2)
+    alive = [1] * src.n_ranks
+    alive[spec.rank_of(src, 0, 0, 1)] = 0
+    with pytest.raises(tpx.TpxError) as ei:
+        plan_for(SMALL, src, Parallel(1, 1, 1), rank_alive=alive)
+    assert ei.value.status == B.TPX_ERR_UNRECOVERABLE
+    plan = plan_for(SMALL, Parallel(2, 1, 2), Parallel(1, 1, 1), rank_alive=alive)      # fully replicated: fine
+    assert all(alive[b.src_rank] for b in plan.boxes())
+    with pytest.raises(tpx.TpxError) as ei:                                              # a kind the model lacks
+        plan_for(SMALL, Parallel(2, 1, 2, shard_kinds=4), Parallel(1, 1, 1))
+    assert ei.value.status == B.TPX_ERR_INVALID_ARG
 
 
 # ---- error codes ----------------------------------------------------------------------------------

@@ -44,7 +44,9 @@ def random_case(rng):
             stages = tuple([0] + cuts + [layers])
         else:
             stages = None
-        return Parallel(T, P, D, stages, qkv_layout=rng.choice([0, 0, 1]), w_transposed=rng.choice([0, 0, 0, 1]))
+        shard = rng.randrange(1 << len(kinds)) if D > 1 and rng.random() < 0.5 else 0    # kinds cut over the replicas
+        return Parallel(T, P, D, stages, qkv_layout=rng.choice([0, 0, 1]), w_transposed=rng.choice([0, 0, 0, 1]),
+                        shard_kinds=shard)
     return model, par(), par()
 
 

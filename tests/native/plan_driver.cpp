@@ -85,6 +85,20 @@ int main() {
   plan_and_walk(model(4, 24, 12, 48, 36, 0, 4, TPX_MODEL_TIED_HEAD), par(2, 2, 2), par(3, 4, 1, nullptr, 1, 1), 1);
   plan_and_walk(model(4, 24, 12, 48, 50, 4, 3), par(4, 1, 1, nullptr, 1, 1), par(3, 2, 3), 1);
   plan_and_walk(model(8, 64, 8, 128, 64, 0, 4), par(8, 4, 4), par(4, 8, 4), 1);
+  {  // state kinds cut over the replicas, odd replica counts, with and without share_reads
+    tpx_parallel a = par(2, 2, 3), b = par(4, 1, 5, nullptr, 1, 1), c = par(1, 2, 7);
+    a.shard_kinds = 14; b.shard_kinds = 6; c.shard_kinds = 15;
+    plan_and_walk(model(4, 24, 12, 48, 36, 0, 4), a, b, 1);
+    plan_and_walk(model(4, 24, 12, 48, 36, 0, 4), b, c, 1);
+    CHECK(tpx_set_option("share_reads", 1) == TPX_OK);
+    plan_and_walk(model(4, 24, 12, 48, 36, 0, 4), c, a, 1);
+    plan_and_walk(model(24, 2048, 16, 8192, 50304, 0, 4), par(4, 2, 2), par(4, 2, 8), 19);
+    CHECK(tpx_set_option("share_reads", 0) == TPX_OK);
+    tpx_parallel bad = par(2, 1, 2);
+    bad.shard_kinds = 16;
+    tpx_plan_t* p = nullptr;
+    CHECK(tpx_plan(&(const tpx_model&)model(4, 24, 12, 48, 36, 0, 4), &bad, &a, &p) == TPX_ERR_INVALID_ARG);
+  }
   const uint8_t alive[8] = {0, 0, 1, 1, 1, 1, 0, 0};
   plan_and_walk(model(4, 24, 12, 48, 36, 0, 4), par(2, 2, 2, nullptr, 0, 0, alive), par(2, 1, 1), 1);
   for (uint64_t tb : {4096ull, 65536ull, 4194304ull}) {

@@ -2,6 +2,8 @@
 consumption (independent of the oracle's index formula) and the consistency
 requirements the paper states (sections 1 and 2.2: every sample exactly once per
 epoch, consumption order unchanged by a re-partitioning, constant global batch)."""
+import os
+
 import numpy as np
 import pytest
 
@@ -82,3 +84,15 @@ def test_inconsistent_cursors_are_rejected():
         ods.repartition(parts, [7, 7, 7, 7], 24, 2)
     with pytest.raises(ValueError):
         ods.partition(G, 25, 4)
+
+
+def test_hand_worked_two_to_four_replicas_golden():
+    path = os.path.join(os.path.dirname(__file__), "golden", "dataset_d2_to_d4.txt")
+    rows = [[int(x) for x in line.split()] for line in open(path) if line.strip() and not line.startswith("#")]
+    two, four, cur2, cur4 = rows[0:2], rows[2:6], rows[6], rows[7]
+    G = np.arange(11, dtype=np.uint64)
+    assert [list(map(int, p)) for p in ods.partition(G, 4, 2)] == two
+    assert [list(map(int, p)) for p in ods.partition(G, 4, 4)] == four
+    assert ods.cursors_after(11, 4, 2, 1) == cur2
+    parts, cur = ods.repartition([np.array(p, dtype=np.uint64) for p in two], cur2, 4, 4)
+    assert [list(map(int, p)) for p in parts] == four and cur == cur4

@@ -444,6 +444,21 @@ def test_pins_catch_a_plain_row_split_of_qkv_major(monkeypatch):
         test_tensor_parallel_forward_equivalence(Parallel(3, 1, 1, qkv_layout=1, w_transposed=0))
 
 
+def test_sharded_kind_hand_worked_golden():
+    rows = _load_golden("sharded_kind_5rows_3replicas.txt")
+    block = np.arange(10, 20).reshape(5, 2)
+    for D, want in ((3, rows[0:3]), (4, rows[3:6] + [None])):
+        for d in range(D):
+            got = spec.replica_range((0, 0), (5, 2), (0, 1), D, d)
+            if want[d] is None:
+                assert got is None
+            else:
+                lo, hi = got
+                assert block[lo[0]:hi[0], lo[1]:hi[1]].reshape(-1).tolist() == want[d]
+    # the outermost *stored* axis is cut: a block stored column-major is cut by columns
+    assert spec.replica_range((0, 0), (5, 2), (1, 0), 2, 1) == ((0, 1), (5, 2))
+
+
 def test_pins_catch_floor_sized_replica_chunks(monkeypatch):
     """Planted mistake: chunks of floor(n / D) rows leave the tail of a sharded tensor with no holder."""
     real = spec.replica_range

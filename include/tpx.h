@@ -250,7 +250,10 @@ tpx_status tpx_execute(tpx_plan_t*, const void* const* src_bufs, void* const* ds
                        void* workspace, void* hip_stream);
 
 /* Optional: copy the plan tables into `workspace` now (and wait for the copy), so that a following
- * tpx_execute with the same workspace only launches the kernel.  Errors: INVALID_ARG, HIP. */
+ * tpx_execute with the same workspace only launches the kernel.  Required before a tpx_execute that is
+ * recorded into a HIP graph (stream capture allows neither the wait nor a copy from pageable host memory):
+ * prepare outside the capture, then capture the execute, which is then a single kernel node.
+ * Errors: INVALID_ARG, HIP. */
 tpx_status tpx_prepare(tpx_plan_t*, void* workspace, void* hip_stream);
 
 /* Forget which workspace holds the plan tables (call after overwriting or freeing it). */

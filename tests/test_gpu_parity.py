@@ -319,6 +319,36 @@ def test_paper_reconfiguration_pairs(cuda, name):
     torch.cuda.empty_cache()
 
 
+def test_shared_reads_full_size(cuda):
+    """BERT-large-shape (1,1,4) -> (1,1,8) with share_reads: one 8-way multicast move per piece, every replica
+    complete (closed form), gaps untouched, one fifth of the reads of the locality plan."""
+    import bench
+    mk_, s_, d_, _, seed = bench.WORKLOADS["bert-large_(1,1,4)->(1,1,8)"]
+    model = Model(mk_["n_layers"], mk_["hidden"], mk_["n_heads"], mk_["ffn"], mk_["vocab_true"], mk_.get("max_pos", 1024),
+                  mk_.get("vocab_divisor", 0), tuple(mk_["state_elem_bytes"]))
+    src, dst = Parallel(1, 1, 4), Parallel(1, 1, 8)
+    local = plan_for(model, src, dst).stats()
+    tpx.tpx_set_option("share_reads", 1)
+    try:
+        plan = plan_for(model, src, dst)
+    finally:
+        tpx.tpx_set_option("share_reads", 0)
+    st = plan.stats()
+    assert st["bytes_written"] == local["bytes_written"] == 8 * st["bytes_read"] and local["bytes_read"] == 5 * st["bytes_read"]
+    src_gpu = []
+    for descs, n in H.manifest_descs(model, src):
+        b = G.alloc(n, H.SRC_GAP)
+        synth.fill_buffer(b, descs, seed, synth.MIX_GPT)
+        src_gpu.append(b)
+    got, _ = G.execute(plan, src_gpu)
+    torch.cuda.synchronize()
+    assert H.closed_form_mismatches(got, model, src, dst, seed, synth.MIX_GPT) == 0
+    for b, (descs, n) in zip(got, H.manifest_descs(model, dst)):
+        assert H.gaps_untouched(b, descs, H.POISON)
+    del got, src_gpu
+    torch.cuda.empty_cache()
+
+
 def test_multicast_small(cuda):
     """Replicated destinations on odd-sized models: copy, fill and transposing tiles with several destinations."""
     _check_small(SMALL, SMALL_MIX, Parallel(2, 2, 1), Parallel(2, 2, 3))

@@ -1,0 +1,37 @@
+"""bench.py's output contract, checked on the smallest workload (GPU) and its refusal of several GPUs (anywhere)."""
+import json
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_more_than_one_gpu_is_refused():
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, cwd=ROOT)
+    assert r.returncode != 0 and "one GPU" in r.stderr and not r.stdout.strip()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("workload", ["tiny_2L_h256_(2,1,1)->(4,2,1)", "dataset_1e8_D6->D4"])
+def test_bench_prints_one_json_line_with_the_contract_fields(cuda, workload):
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--workload", workload, "--steps", "3", "--warmup", "1"],
+                       capture_output=True, text=True, cwd=ROOT, timeout=600)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [l for l in r.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    assert d["metric"] == "reshard_GBps_state_bytes_read_plus_written" and d["unit"] == "GB/s"
+    assert d["n_gpus"] == 1 and d["steps"] == 3 and d["warmup"] == 1 and d["higher_is_better"] is True
+    assert d["scaling"] == "weak" and d["vs_baseline"] is None and d["data"] == "synthetic" and d["dtype"] in ("u8", "u64")
+    assert d["config"]["workload"] == workload and "model" not in d["config"]
+    assert d["value"] > 0 and d["ms_per_step"] > 0
+    assert abs(d["value"] - (d["config"]["state_bytes_read"] + d["config"]["state_bytes_written"]) / d["ms_per_step"] / 1e6) <= 0.01 * d["value"] + 0.1
+    roof = d["roofline"]
+    assert roof["bound"] == "hbm" and roof["unit"] == "GB/s" and roof["peak"] == 8000.0 and "traffic" in roof
+    assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-3
+    cpu = d["cpu_baseline"]
+    assert cpu["kind"] == "oracle" and cpu["unit"] == "GB/s" and cpu["value"] > 0 and cpu["cores"] >= 1 and cpu["sample"]
+    assert cpu["gpu_matches_oracle_on_sample"] is True

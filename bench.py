@@ -87,6 +87,7 @@ MEASURED_TRAFFIC = {
     "gpt_h3072_T3->T4_padded_vocab": 80869000000,
     "gpt1.3b_(4,2,1)->(4,2,2)_dp": 55526000000,
     "bert-large_(1,1,4)->(1,1,8)": 60847000000,
+    "gpt2.7b_(2,2,4)->(4,2,2)_sharded_opt": 85078000000,
     "bert-large_(1,1,4)->(1,1,8)|share_reads": 42149670154,
     "gpt1.3b_(4,2,1)->(2,4,1)_transposed_dst": 36855000000,
 }

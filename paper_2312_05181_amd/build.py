@@ -11,6 +11,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtpx.so")
+SELFTEST_SRC = os.path.join(ROOT, "examples", "reshard_selftest.cpp")
+SELFTEST = os.path.join(HERE, "tpx_selftest")
 HOST_SOURCES = ["layout.cpp", "planner.cpp", "dataset.cpp", "api.cpp"]
 HIP_SOURCES = ["kernels.hip"]
 # the host pass does not know the device-only feature flag and says so once per file: harmless noise
@@ -49,6 +51,9 @@ def build(verbose: bool = True) -> str:
         list(ex.map(lambda c: _run(c, verbose), jobs))
     objs = [os.path.join(OBJ, s + ".o") for s in HOST_SOURCES + HIP_SOURCES]
     _run([hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB, *objs], verbose)
+    # a stand-alone user of the C ABI (host code only; finds libtpx.so next to itself)
+    _run([hipcc(), "-O2", "-std=c++17", "-I", os.path.join(ROOT, "include"), SELFTEST_SRC, "-L", HERE, "-ltpx",
+          "-Wl,-rpath,$ORIGIN", "-o", SELFTEST], verbose)
     return LIB
 
 

@@ -1,4 +1,5 @@
-"""bench.py's output contract, checked on the smallest workload (GPU) and its refusal of several GPUs (anywhere)."""
+"""bench.py's output contract, checked on the smallest workloads (GPU), its refusal of several GPUs (anywhere), and the
+stand-alone C program that uses the library without Python."""
 import json
 import os
 import subprocess
@@ -35,3 +36,14 @@ def test_bench_prints_one_json_line_with_the_contract_fields(cuda, workload):
     cpu = d["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["unit"] == "GB/s" and cpu["value"] > 0 and cpu["cores"] >= 1 and cpu["sample"]
     assert cpu["gpu_matches_oracle_on_sample"] is True
+
+
+@pytest.mark.gpu
+def test_c_abi_without_python_or_torch(cuda):
+    """examples/reshard_selftest.cpp, built next to the library: plans, executes and checks a reshard through the
+    C ABI alone, with the system's HIP runtime."""
+    exe = os.path.join(ROOT, "paper_2312_05181_amd", "tpx_selftest")
+    assert os.path.exists(exe), "build it with python -m paper_2312_05181_amd.build"
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, (r.stdout + r.stderr)[-2000:]
+    assert " 0 wrong" in r.stdout

@@ -274,7 +274,8 @@ void tpx_free(tpx_plan_t*);
 /* Description of the last failure on the calling thread (never NULL; valid until that thread's next failure). */
 const char* tpx_last_error(void);
 
-/* Global tuning knobs, read by later tpx_plan / tpx_execute calls on any thread:
+/* Global tuning knobs, read by later tpx_plan / tpx_execute calls on any thread (each knob is read and written
+ * atomically; a plan being made while a knob changes sees the old or the new value):
  *   "tile_bytes"  upper bound of bytes per tile (power of two, 4096 .. 4194304; default 131072); small jobs
  *                 use smaller tiles, down to 16384, so that the launch still has thousands of workgroups
  *   "variant"     kernel variant, 0 (default) = chosen from the tile size: 1024 threads per workgroup with eight

@@ -406,7 +406,7 @@ tpx_status hip_launch_tiles(const void* workspace, const tpx_plan_s& plan, const
   }
   // interleaving several parts of the plan pays only when tiles cost the same; a plan that mixes plain and
   // replicated moves, or has transposing tiles, runs in plan order
-  const uint32_t streams = plan.uniform_tiles && !(automatic && plan.needs_lds) ? uint32_t(std::max<uint64_t>(1, tuning().streams)) : 1;
+  const uint32_t streams = plan.uniform_tiles && !(automatic && plan.needs_lds) ? uint32_t(std::max<uint64_t>(1, tuning().streams.load())) : 1;
   const uint32_t grid = uint32_t((plan.n_tiles + streams - 1) / streams * streams);
   KernelFn k = pick_kernel(variant);
   hipLaunchKernelGGL(k, dim3(grid), dim3(threads_of(variant)), plan.needs_lds ? kLdsBytes : 0,

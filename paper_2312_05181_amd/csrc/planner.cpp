@@ -166,6 +166,7 @@ tpx_status plan_model_moves(tpx_plan_s& plan) {
   };
   std::vector<Piece> pieces;
   std::vector<std::vector<int>> choice;
+  const uint64_t max_multicast = tuning().max_multicast, share_reads = tuning().share_reads;  // one reading per plan
   auto unrecoverable = [&](const tpx_entry& sn) {
     return fail(TPX_ERR_UNRECOVERABLE, "no surviving holder of a piece of tensor " + std::to_string(sn.tensor_id) +
                                            (sn.name < N_NAMES && S.tp_degree ? std::string(" (") + param_name(sn.name) + ", layer " + std::to_string(sn.layer) + ")" : std::string()));
@@ -234,12 +235,12 @@ tpx_status plan_model_moves(tpx_plan_s& plan) {
     }
     // With every buffer in one GPU's memory "the same device" saves nothing, while one shared source
     // makes the whole group one multicast move: each piece is read once instead of once per distinct choice.
-    if (tuning().share_reads)
+    if (share_reads)
       for (uint32_t dn = 1; dn < g.count; ++dn) choice[dn] = choice[0];
     // one set of moves per run of consecutive members with identical choices
     for (uint32_t d0 = 0; d0 < g.count;) {
       uint32_t d1 = d0 + 1;
-      while (d1 < g.count && d1 - d0 < tuning().max_multicast && choice[d1] == choice[d0]) ++d1;
+      while (d1 < g.count && d1 - d0 < max_multicast && choice[d1] == choice[d0]) ++d1;
       const uint32_t rn = r0 + d0 * g.stride;
       for (size_t i = 0; i < pieces.size(); ++i) emit(pieces[i], choice[d0][i], rn, d1 - d0, g.stride);
       d0 = d1;

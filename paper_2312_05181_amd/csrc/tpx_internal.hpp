@@ -1,6 +1,7 @@
 // Internal declarations shared by the host planner, the C ABI and the HIP executor.
 #pragma once
 
+#include <atomic>
 #include <cstdint>
 #include <string>
 #include <unordered_map>
@@ -96,12 +97,14 @@ tpx_status check_model(const tpx_model& m);
 tpx_status sigma_of(const tpx_model& m, const tpx_parallel& par, uint32_t name, Sigma& out);
 tpx_status build_side(const tpx_model& m, const tpx_parallel& par, Side& out);
 
+// Process-wide knobs (tpx_set_option).  Atomic so that one thread may set them while others plan or execute:
+// each read sees the old or the new value, never a torn one.
 struct Tuning {
-  uint64_t tile_bytes = 131072;
-  uint64_t streams = 4;   // tile order: workgroup b works on contiguous part b % streams of the plan
-  uint64_t max_multicast = 8;  // most destinations one move may be replicated to
-  uint64_t share_reads = 0;    // 1: all members of a replica group read what its first member reads
-  uint64_t variant = 0;   // 0 = chosen from the tile size (1024 threads x 8 nontemporal loads for 128 KiB tiles)
+  std::atomic<uint64_t> tile_bytes{131072};
+  std::atomic<uint64_t> streams{4};        // tile order: workgroup b works on contiguous part b % streams of the plan
+  std::atomic<uint64_t> max_multicast{8};  // most destinations one move may be replicated to
+  std::atomic<uint64_t> share_reads{0};    // 1: all members of a replica group read what its first member reads
+  std::atomic<uint64_t> variant{0};        // 0 = chosen from the tile size (1024 threads x 8 nontemporal loads for 128 KiB tiles)
 };
 Tuning& tuning();
 

@@ -231,6 +231,14 @@ tpx_status tpx_get_tile(const tpx_plan_t*, uint64_t i, tpx_tile* out);
 uint64_t   tpx_num_segments(const tpx_plan_t*);
 tpx_status tpx_get_segment(const tpx_plan_t*, uint64_t i, tpx_segment* out);
 
+/* Traffic matrix of the plan: out[i * n_dst + j] = bytes that destination rank j receives from source rank i
+ * (n_src x n_dst entries, row-major; a move replicated to several destinations counts once per destination;
+ * zero fill has no source and is not counted).  With one device per rank this is the exchange the locality
+ * rule of section 6.5 minimises: the diagonal (i == j) stays on the device, the rest crosses devices
+ * (its sum is tpx_stats.bytes_cross_rank).  `out` is a HOST array of tpx_num_buffers(src) * tpx_num_buffers(dst)
+ * entries.  Errors: INVALID_ARG. */
+tpx_status tpx_traffic(const tpx_plan_t*, uint64_t* out);
+
 /* DEVICE bytes tpx_execute needs in `workspace` (a header, then the plan tables: flat boxes, tile prefix
  * sums, merge segments). */
 uint64_t   tpx_workspace_bytes(const tpx_plan_t*);

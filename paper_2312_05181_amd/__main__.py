@@ -62,6 +62,7 @@ def main(argv=None) -> int:
         out["src_buffer_bytes"] = [plan.buffer_bytes(0, r) for r in range(plan.num_buffers(0))]
         out["dst_buffer_bytes"] = [plan.buffer_bytes(1, r) for r in range(plan.num_buffers(1))]
         out["workspace_bytes"] = plan.workspace_bytes()
+        out["traffic_bytes_src_to_dst"] = plan.traffic()
         print(json.dumps(out))
     else:
         side = 0 if a.side == "src" else 1

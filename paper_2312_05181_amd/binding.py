@@ -108,6 +108,7 @@ _sigs = {
     "tpx_get_tile": (C.c_int, [_P, C.c_uint64, C.POINTER(tpx_tile)]),
     "tpx_num_segments": (C.c_uint64, [_P]),
     "tpx_get_segment": (C.c_int, [_P, C.c_uint64, C.POINTER(tpx_segment)]),
+    "tpx_traffic": (C.c_int, [_P, C.POINTER(C.c_uint64)]),
     "tpx_workspace_bytes": (C.c_uint64, [_P]),
     "tpx_execute": (C.c_int, [_P, C.POINTER(_P), C.POINTER(_P), _P, _P]),
     "tpx_prepare": (C.c_int, [_P, _P, _P]),
@@ -215,6 +216,13 @@ class Plan:
             _check(_lib.tpx_get_segment(self._h, i, C.byref(g)))
             out.append(g)
         return out
+
+    def traffic(self) -> list:
+        """[source rank][destination rank] -> bytes moved between the two buffers."""
+        ns, nd = self.num_buffers(SIDE_SRC), self.num_buffers(SIDE_DST)
+        out = (C.c_uint64 * max(1, ns * nd))()
+        _check(_lib.tpx_traffic(self._h, out))
+        return [[out[i * nd + j] for j in range(nd)] for i in range(ns)]
 
     def workspace_bytes(self) -> int:
         return _lib.tpx_workspace_bytes(self._h)

@@ -1,4 +1,5 @@
 // C ABI of libtpx (declared in tpx.h): argument checking and hand-off to the planner and the HIP executor.
+#include <algorithm>
 #include <atomic>
 #include <chrono>
 #include <cstring>
@@ -185,6 +186,18 @@ uint64_t tpx_num_segments(const tpx_plan_t* p) { return p ? p->segments.size() :
 tpx_status tpx_get_segment(const tpx_plan_t* p, uint64_t i, tpx_segment* out) {
   if (!p || !out || i >= p->segments.size()) return fail(TPX_ERR_INVALID_ARG, "tpx_get_segment: bad argument");
   *out = p->segments[i];
+  return TPX_OK;
+}
+
+tpx_status tpx_traffic(const tpx_plan_t* p, uint64_t* out) {
+  if (!p || !out) return fail(TPX_ERR_INVALID_ARG, "tpx_traffic: NULL argument");
+  const size_t ns = p->side[0].bytes.size(), nd = p->side[1].bytes.size();
+  std::fill(out, out + ns * nd, uint64_t(0));
+  for (const tpx_box& b : p->boxes) {
+    if (b.kind == TPX_BOX_FILL) continue;
+    const uint64_t n = box_bytes(b);
+    for (uint32_t k = 0; k < b.n_dst; ++k) out[size_t(b.src_rank) * nd + b.dst_rank + size_t(k) * b.dst_rank_stride] += n;
+  }
   return TPX_OK;
 }
 

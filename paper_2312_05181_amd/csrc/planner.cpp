@@ -88,13 +88,13 @@ tpx_box lower_piece(const uint64_t lo[4], const uint64_t hi[4], const tpx_entry*
   return b;
 }
 
+}  // namespace
+
 uint64_t box_bytes(const tpx_box& b) {
   uint64_t n = b.run_bytes;
   for (uint32_t i = 0; i < b.ndim; ++i) n *= b.extent[i];
   return n;
 }
-
-}  // namespace
 
 // get_resource(phi, alpha, w): among the surviving old holders of the old sub-tensor that contains
 // piece w, prefer (1) the one whose buffer index equals the destination's (the "same device": nothing

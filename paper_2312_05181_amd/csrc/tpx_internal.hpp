@@ -136,6 +136,7 @@ void       coalesce_boxes(std::vector<tpx_box>& boxes);        // merge neighbou
 tpx_status tile_boxes(tpx_plan_s& plan, uint64_t tile_bytes);  // boxes -> tiles
 tpx_status validate_tiles(tpx_plan_s& plan);                    // every access inside its buffer
 void       finish_stats(tpx_plan_s& plan);
+uint64_t   box_bytes(const tpx_box& b);                          // payload of one move (per destination)
 tpx_status plan_dataset_moves(tpx_plan_s& plan, uint64_t n_samples, uint32_t B, uint32_t elem_bytes,
                               uint32_t D_src, uint32_t D_dst, const uint64_t* src_cursors,
                               std::vector<uint64_t>& dst_cursors);

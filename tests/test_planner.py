@@ -235,6 +235,38 @@ def test_share_reads_reads_every_piece_once(src, dst):
     assert {b.n_dst for b in plan.boxes()} == ({8, dst.D % 8} - {0} if dst.D > 8 else {dst.D})
 
 
+@pytest.mark.parametrize("model,mix,src,dst", PAIRS)
+def test_traffic_matrix_accounts_for_every_moved_byte(model, mix, src, dst):
+    """tpx_traffic: column sums = bytes each destination rank receives (its tensor bytes minus zero fill), the
+    off-diagonal sum = bytes_cross_rank, and lost or absent pairs are zero."""
+    plan = plan_for(model, src, dst)
+    m = plan.traffic()
+    s = plan.stats()
+    assert len(m) == src.n_ranks and all(len(row) == dst.n_ranks for row in m)
+    assert sum(map(sum, m)) == s["bytes_written"] - s["bytes_fill"]
+    assert sum(m[i][j] for i in range(src.n_ranks) for j in range(dst.n_ranks) if i != j) == s["bytes_cross_rank"]
+    want = [np.zeros(dst.n_ranks, dtype=np.int64) for _ in range(src.n_ranks)]
+    for b in plan.boxes():
+        if b.kind != B.BOX_FILL:
+            n = b.run_bytes * int(np.prod([b.extent[k] for k in range(b.ndim)], dtype=np.int64))
+            for k in range(b.n_dst):
+                want[b.src_rank][b.dst_rank + k * b.dst_rank_stride] += n
+    assert [list(map(int, row)) for row in want] == m
+    if model.vocab_divisor == 0:          # no zero fill: every destination receives exactly its tensor bytes
+        for j in range(dst.n_ranks):
+            mine = sum(H.desc_of(e).nbytes for e in spec.rank_manifest(model, dst, j)[0])
+            assert sum(m[i][j] for i in range(src.n_ranks)) == mine
+
+
+def test_traffic_of_a_pipeline_only_change_is_block_structured():
+    """(4,2,1) -> (4,4,1): destination stage p' of tensor-parallel rank t receives only from old stage p'//2, same t."""
+    plan = plan_for(H.GPT_1_3B, Parallel(4, 2, 1), Parallel(4, 4, 1))
+    m = plan.traffic()
+    for i in range(8):
+        for j in range(16):
+            assert (m[i][j] > 0) == (i % 4 == j % 4 and i // 4 == (j // 4) // 2), (i, j)
+
+
 def _identity_maps(model, par, mix):
     """Per rank: int64 array with a unique id (tensor, kind, position) per element slot of 2 bytes."""
     out = []

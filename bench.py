@@ -74,6 +74,14 @@ SHARDED_PAIRS = {
     "gpt1.3b_(4,1,4)->(2,2,2)_sharded_opt": (_G13, _c(4, 1, 4, shard_kinds=14), _c(2, 2, 2, shard_kinds=14), "gpt", 32),
 }
 WORKLOADS.update(SHARDED_PAIRS)
+# failure recovery (section 5.3): one replica of every (t, p) share of (4,2,2) is lost; only those eight ranks are
+# rebuilt, each from its surviving replica
+_LOST = [1 if (r % 4 + r // 8) % 2 == (r // 4) % 2 else 0 for r in range(16)]      # rank = t + 4*(d + 2*p)
+RECOVERY = {
+    "gpt2.7b_(4,2,2)_rebuild_8_lost_of_16": (_G27, _c(4, 2, 2, rank_alive=[1 - x for x in _LOST]),
+                                             _c(4, 2, 2, rank_alive=_LOST), "gpt", 41),
+}
+WORKLOADS.update(RECOVERY)
 DATASET_WORKLOAD = "dataset_1e8_D6->D4"
 DATASET_CFG = dict(n_samples=10 ** 8, global_batch=768, D_src=6, D_dst=4, steps_done=65000, seed=6)
 DEFAULT_WORKLOAD = "gpt6.7b_(8,1,1)->(1,8,1)"
@@ -398,8 +406,11 @@ def cpu_baseline(args, model, src, dst, plan, src_bufs, dst_bufs, src_ptrs, dst_
     plan.execute(src_ptrs, dst_ptrs, ws.data_ptr(), stream)
     torch.cuda.synchronize()
     ok = True
+    built = dst.get("rank_alive")
     for tk, outs in results.items():
         for rank, e, block in outs:
+            if built is not None and not built[rank]:
+                continue                      # a destination rank that is not rebuilt
             moved += 2 * block.nbytes
             have = dst_bufs[rank][e.offset:e.offset + block.nbytes].cpu().numpy()
             ok = ok and bool(np.array_equal(have, block.reshape(-1).view(np.uint8)))

@@ -68,8 +68,10 @@ typedef struct {
   const uint32_t* stage_first_layer; /* phi: P+1 ascending layer boundaries, [0]=0, [P]=n_layers; NULL = n_layers/P each */
   uint32_t qkv_layout;               /* sigma of the fused QKV tensors: 0 head-major [a,3,d,*], 1 qkv-major [3,a,d,*] */
   uint32_t w_transposed;             /* 1: 2-D weights are stored [in, out] instead of [out, in] */
-  const uint8_t* rank_alive;         /* T*P*D bytes, 0 = this rank's buffer is lost (section 5.3); NULL = all alive.
-                                        Only meaningful for the source configuration. */
+  const uint8_t* rank_alive;         /* T*P*D bytes or NULL (= all 1).  Source configuration: 0 = this rank's buffer is
+                                        lost (section 5.3) and is never read.  Destination configuration: 0 = this rank
+                                        is not to be built (say, it survived and keeps its state): no move is planned
+                                        for it, its buffer is never written and may be NULL in tpx_execute. */
   uint32_t shard_kinds;              /* phi, sharded data parallelism: bit k set = state kind k is not replicated over
                                         the D replicas but cut between them: of each block its (t, p) share holds,
                                         replica d stores chunk d of ceil(n / D) rows along the block's outermost
@@ -191,7 +193,8 @@ typedef struct {
   const uint32_t* n_entries;        /* n_ranks counts */
   const tpx_entry* const* entries;  /* n_ranks arrays */
   const uint64_t* rank_bytes;       /* n_ranks buffer sizes, or NULL: end of the last sub-tensor rounded up to 256 */
-  const uint8_t* rank_alive;        /* n_ranks flags, 0 = lost (source only), or NULL */
+  const uint8_t* rank_alive;        /* n_ranks flags or NULL: source 0 = lost, destination 0 = not to be built
+                                       (as in tpx_parallel) */
 } tpx_ptc;
 
 /* Plan the transformation of PTC src into PTC dst over the same tensors (algorithm 1).  Within one side the
@@ -246,8 +249,8 @@ uint64_t   tpx_workspace_bytes(const tpx_plan_t*);
 /* Apply the plan (section 5.1, step 4): one kernel launch on `hip_stream` (a hipStream_t, NULL = the
  * default stream).  src_bufs / dst_bufs are HOST arrays of DEVICE pointers, one per rank of the side,
  * each at least tpx_buffer_bytes() long and 16-byte aligned (256 recommended); entries of lost source
- * ranks may be NULL.  workspace is a DEVICE pointer to tpx_workspace_bytes() bytes, 64-byte aligned.
- * Every destination tensor byte is written exactly once; bytes between tensors are left untouched;
+ * ranks and of destination ranks that are not built (rank_alive) may be NULL.  workspace is a DEVICE pointer to tpx_workspace_bytes() bytes, 64-byte aligned.
+ * Every tensor byte of every destination rank that is built is written exactly once; bytes between tensors are left untouched;
  * sources are only read and must not overlap destinations.  The call does not wait for the kernel.
  * The first call with a given workspace copies the plan tables into it and waits for that copy;
  * later calls with the same workspace reuse it, so the caller must not modify the workspace in

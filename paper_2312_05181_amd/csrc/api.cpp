@@ -222,7 +222,8 @@ tpx_status tpx_execute(tpx_plan_t* p, const void* const* src_bufs, void* const* 
     if (reinterpret_cast<uintptr_t>(src_bufs[r]) % 16) return fail(TPX_ERR_INVALID_ARG, "tpx_execute: source buffer not 16-byte aligned");
   }
   for (uint32_t r = 0; r < nd; ++r) {
-    if (!dst_bufs[r] && p->side[1].bytes[r]) return fail(TPX_ERR_INVALID_ARG, "tpx_execute: NULL destination buffer");
+    if (!dst_bufs[r] && p->side[1].alive[r] && p->side[1].bytes[r])
+      return fail(TPX_ERR_INVALID_ARG, "tpx_execute: NULL destination buffer for a rank that is to be built");
     if (reinterpret_cast<uintptr_t>(dst_bufs[r]) % 16) return fail(TPX_ERR_INVALID_ARG, "tpx_execute: destination buffer not 16-byte aligned");
   }
   if (p->n_tiles == 0) return TPX_OK;

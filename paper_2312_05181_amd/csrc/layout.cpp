@@ -302,8 +302,8 @@ tpx_status index_subs(Side& side) {
   return TPX_OK;
 }
 
-// Partitions the ranks into replica groups: ranks with identical manifests whose indices form an
-// arithmetic progression.
+// Partitions the wanted ranks (alive != 0) into replica groups: ranks with identical manifests whose indices
+// form an arithmetic progression.
 tpx_status find_groups(Side& side) {
   side.groups.clear();
   std::vector<char> done(side.ranks.size(), 0);
@@ -317,6 +317,8 @@ tpx_status find_groups(Side& side) {
     }
     return true;
   };
+  for (uint32_t r = 0; r < side.ranks.size(); ++r)
+    if (!side.alive[r]) done[r] = 1;  // a destination rank that is not to be built belongs to no group: nothing is planned for it
   for (uint32_t r = 0; r < side.ranks.size(); ++r) {
     if (done[r]) continue;
     ReplicaGroup g{r, 1, 0};

@@ -463,6 +463,7 @@ tpx_status validate_tiles(tpx_plan_s& plan) {
       const uint32_t r = t.dst_rank + k * t.dst_rank_stride;
       if (r >= plan.side[1].bytes.size() || dlast > plan.side[1].bytes[r])
         return fail(TPX_ERR_INVALID_ARG, "internal: a move writes outside its destination buffer");
+      if (!plan.side[1].alive[r]) return fail(TPX_ERR_INVALID_ARG, "internal: a move targets a rank that is not to be built");
     }
     if (t.kind == TPX_TILE_MERGE) {
       if (!t.n_seg || uint64_t(t.n_seg) * t.seg_units != t.run_units || uint64_t(t.seg_first) + t.n_seg > plan.segments.size())

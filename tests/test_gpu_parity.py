@@ -111,6 +111,32 @@ def test_failure_recovery_reads_only_survivors(cuda):
     assert all(np.array_equal(g.cpu().numpy(), w) for g, w in zip(got, want))
 
 
+def test_rebuild_only_the_lost_ranks(cuda):
+    """(4,2,2) with one replica of every share lost: only those eight ranks are rebuilt; the survivors' destination
+    pointers are NULL and nothing is written for them."""
+    model, mix = SMALL, SMALL_MIX
+    cfg = Parallel(4, 2, 2)
+    gone = {spec.rank_of(cfg, t, p, (t + p) % 2) for t in range(4) for p in range(2)}
+    alive = [0 if r in gone else 1 for r in range(16)]
+    need = [1 - a for a in alive]
+    src_cpu = H.make_src_bufs(model, cfg, 5, mix)
+    want = oreshard.reshard(model, cfg, cfg, H.np_bufs(src_cpu))
+    plan = plan_for(model, cfg, cfg, dst_alive=need, rank_alive=alive)
+    empty = torch.empty(0, dtype=torch.uint8, device="cuda")
+    src_gpu = [b.cuda() if alive[r] else empty for r, b in enumerate(src_cpu)]
+    dst_gpu = [G.alloc(plan.buffer_bytes(1, r), H.POISON) if need[r] else empty for r in range(16)]
+    G.execute(plan, src_gpu, dst_bufs=dst_gpu)
+    torch.cuda.synchronize()
+    for r in range(16):
+        if need[r]:
+            assert np.array_equal(dst_gpu[r].cpu().numpy(), want[r]), r
+    with pytest.raises(tpx.TpxError):        # a rank that is to be built needs its buffer
+        bad = list(dst_gpu)
+        bad[min(gone)] = empty
+        G.execute(plan, src_gpu, dst_bufs=bad)
+    torch.cuda.synchronize()
+
+
 def test_execute_argument_errors(cuda):
     plan = plan_for(SMALL, Parallel(2, 1, 1), Parallel(1, 1, 1))
     src = [G.alloc(plan.buffer_bytes(0, r), 0) for r in range(2)]

@@ -31,8 +31,8 @@ def pk(par: Parallel, **extra) -> dict:
     return d
 
 
-def plan_for(model, src, dst, **kw):
-    return tpx.tpx_plan(mk(model), pk(src, **kw), pk(dst))
+def plan_for(model, src, dst, dst_alive=None, **kw):
+    return tpx.tpx_plan(mk(model), pk(src, **kw), pk(dst, rank_alive=dst_alive) if dst_alive is not None else pk(dst))
 
 
 def test_library_exports_every_declared_symbol():
@@ -326,6 +326,53 @@ def test_unrecoverable_when_no_holder_survives():
     with pytest.raises(tpx.TpxError) as ei:
         plan_for(SMALL, src, Parallel(1, 1, 1), rank_alive=alive)
     assert ei.value.status == B.TPX_ERR_UNRECOVERABLE
+
+
+@pytest.mark.parametrize("lost", [4, 8, 12])
+def test_rebuild_only_the_lost_ranks_of_sixteen(lost):
+    """Section 5.3 / 6.4 shape: (T,P,D) = (4,2,2), 16 ranks, some lost.  Only the lost ranks are rebuilt (the
+    destination mask), from the surviving replica of each; with both replicas of a (t, p) share gone the state
+    is unrecoverable."""
+    model, mix = SMALL, SMALL_MIX
+    cfg = Parallel(4, 2, 2)
+    rng = np.random.default_rng(lost)
+    # lose `lost` ranks but never both replicas of one (t, p) share
+    shares = [(t, p) for p in range(2) for t in range(4)]
+    gone = set()
+    if lost <= 8:
+        for t, p in [shares[i] for i in rng.permutation(8)[:lost]]:
+            gone.add(spec.rank_of(cfg, t, p, int(rng.integers(2))))
+    else:
+        for t, p in shares:
+            gone.add(spec.rank_of(cfg, t, p, int(rng.integers(2))))
+        gone |= set(int(x) for x in rng.permutation([r for r in range(16) if r not in gone])[:lost - 8])
+    alive = [0 if r in gone else 1 for r in range(16)]
+    need = [1 - a for a in alive]
+    if lost > 8:
+        with pytest.raises(tpx.TpxError) as ei:
+            plan_for(model, cfg, cfg, dst_alive=need, rank_alive=alive)
+        assert ei.value.status == B.TPX_ERR_UNRECOVERABLE
+        return
+    plan = plan_for(model, cfg, cfg, dst_alive=need, rank_alive=alive)
+    boxes = plan.boxes()
+    assert all(alive[b.src_rank] and need[b.dst_rank] for b in boxes)
+    src_bufs = H.np_bufs(H.make_src_bufs(model, cfg, 5, mix))
+    want = oreshard.reshard(model, cfg, cfg, src_bufs)
+    for r in gone:
+        src_bufs[r][:] = 0xEE
+    got = [np.full(plan.buffer_bytes(1, r), H.POISON, dtype=np.uint8) for r in range(16)]
+    host_exec.run_tiles(plan, src_bufs, got)
+    for r in range(16):
+        if need[r]:
+            assert np.array_equal(got[r], want[r]), r
+        else:
+            assert (got[r] == H.POISON).all(), r                      # survivors are left alone
+    s = plan.stats()
+    rank_bytes = [sum(H.desc_of(e).nbytes for e in spec.rank_manifest(model, cfg, r)[0]) for r in range(16)]
+    rebuilt = sum(rank_bytes[r] for r in gone)
+    assert s["bytes_written"] == rebuilt == s["bytes_read"] == s["bytes_cross_rank"]
+    m = plan.traffic()
+    assert all(sum(m[i][j] for i in range(16)) == (rank_bytes[j] if need[j] else 0) for j in range(16))
 
 
 def test_sharded_kinds_have_no_replica_to_recover_from():

@@ -289,10 +289,11 @@ def _ptc_struct(manifests, rank_bytes=None, rank_alive=None):
     return c, keep
 
 
-def tpx_plan_ptc(src_manifests, dst_manifests, src_bytes=None, dst_bytes=None, src_alive=None) -> Plan:
-    """Plan between two explicitly given collections (any sharding expressible as boxes of tensors)."""
+def tpx_plan_ptc(src_manifests, dst_manifests, src_bytes=None, dst_bytes=None, src_alive=None, dst_alive=None) -> Plan:
+    """Plan between two explicitly given collections (any sharding expressible as boxes of tensors).
+    src_alive: 0 = that source rank is lost; dst_alive: 0 = that destination rank is not to be built."""
     s, keep_s = _ptc_struct(src_manifests, src_bytes, src_alive)
-    d, keep_d = _ptc_struct(dst_manifests, dst_bytes)
+    d, keep_d = _ptc_struct(dst_manifests, dst_bytes, dst_alive)
     h = _P()
     _check(_lib.tpx_plan_ptc(C.byref(s), C.byref(d), C.byref(h)))
     del keep_s, keep_d

@@ -218,6 +218,19 @@ def test_lost_rank_with_replica_is_recovered():
     assert all(np.array_equal(g, w) for g, w in zip(got, want))
 
 
+def test_only_wanted_destination_ranks_are_built():
+    src, dst = sequence(2), sequence(4)
+    a = H.np_bufs(src_buffers(src, 3))
+    want = oreshard.reshard_ptc(src, dst, a)
+    plan = plan_of(src, dst, dst_alive=[0, 1, 0, 1])
+    assert {b.dst_rank for b in plan.boxes()} == {1, 3}
+    got = [np.full(n, H.POISON, dtype=np.uint8) for _, n in dst]
+    host_exec.run_tiles(plan, a, got)
+    assert np.array_equal(got[1], want[1]) and np.array_equal(got[3], want[3])
+    assert (got[0] == H.POISON).all() and (got[2] == H.POISON).all()
+    assert plan.stats()["bytes_written"] == sum(H.desc_of(e).nbytes for r in (1, 3) for e in dst[r][0])
+
+
 @pytest.mark.gpu
 @pytest.mark.parametrize("name", list(CASES))
 def test_generic_gpu_matches_oracle(cuda, name):

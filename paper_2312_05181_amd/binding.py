@@ -300,6 +300,37 @@ def tpx_plan_ptc(src_manifests, dst_manifests, src_bytes=None, dst_bytes=None, s
     return Plan(h.value)
 
 
+class _QueryEntry:
+    def __init__(self, like, lo, hi, offset):
+        self.tensor_id, self.kind, self.elem_bytes, self.full_shape = like.tensor_id, like.kind, like.elem_bytes, tuple(like.full_shape)
+        self.lo, self.hi, self.offset = tuple(lo), tuple(hi), offset
+        self.perm = tuple(range(len(self.full_shape)))      # dense, canonical axis order
+
+
+def tpx_plan_query(src_manifests, queries, src_bytes=None, src_alive=None) -> Plan:
+    """Range queries on a stored collection (paper section 5.2: "/2/embedding/weight[:, 2:4]"): queries is a list of
+    (tensor_id, kind, lo, hi) boxes in the full tensors' coordinates; the plan gathers them, from whichever ranks
+    hold the pieces, into ONE destination buffer, each box dense row-major, one after the other at 256-byte
+    boundaries (plan.manifest(1, 0) gives the offsets).  Marshalling only: it is tpx_plan_ptc with a
+    one-rank destination."""
+    by_tensor = {}
+    for man in src_manifests:
+        for d in man:
+            by_tensor.setdefault((d.tensor_id, d.kind), d)
+    dst, off = [], 0
+    for tensor_id, kind, lo, hi in queries:
+        if (tensor_id, kind) not in by_tensor:
+            raise TpxError(TPX_ERR_INVALID_ARG, f"tensor {tensor_id} kind {kind} is not in the collection")
+        like = by_tensor[(tensor_id, kind)]
+        off = -(-off // 256) * 256
+        dst.append(_QueryEntry(like, lo, hi, off))
+        n = like.elem_bytes
+        for l, h in zip(lo, hi):
+            n *= h - l
+        off += n
+    return tpx_plan_ptc(src_manifests, [dst], src_bytes=src_bytes, src_alive=src_alive)
+
+
 def tpx_plan_dataset(n_samples: int, global_batch: int, D_src: int, D_dst: int, src_cursors: Sequence[int],
                      index_elem_bytes: int = 8) -> Plan:
     if len(src_cursors) != D_src:

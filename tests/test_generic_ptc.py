@@ -218,6 +218,34 @@ def test_lost_rank_with_replica_is_recovered():
     assert all(np.array_equal(g, w) for g, w in zip(got, want))
 
 
+def test_range_queries_gather_sub_tensors_from_their_holders():
+    """Section 5.2's range query: arbitrary boxes of tensors of a (T,P,D) = (3,2,1) job gathered into one dense buffer;
+    expected = the same slice of the full tensor the oracle reassembles."""
+    from oracle import spec
+    from tests.test_planner import SMALL, SMALL_MIX
+    model, par = SMALL, spec.Parallel(3, 2, 1, w_transposed=1)
+    src = [spec.rank_manifest(model, par, r) for r in range(par.n_ranks)]
+    bufs = H.np_bufs(H.make_src_bufs(model, par, 8, SMALL_MIX))
+    lay = oreshard.Layout(manifests=src)
+    dense = spec.tensor_id(spec.DENSE_W, 1)
+    qkv = spec.tensor_id(spec.QKV_W, 3)
+    queries = [(dense, 0, (0, 2), (24, 4)),            # weight[:, 2:4] of a row-parallel tensor: columns of one shard
+               (dense, 1, (5, 6), (9, 20)),            # a box that spans all three shards
+               (qkv, 1, (3, 1, 0, 7), (10, 3, 2, 19)),  # heads 3..9, K and V, both rows of each head
+               (0, 0, (10, 0), (30, 24))]              # embedding rows from two vocabulary shards
+    plan = tpx.tpx_plan_query([[H.desc_of(e) for e in ent] for ent, _ in src], queries, src_bytes=[n for _, n in src])
+    assert plan.num_buffers(1) == 1
+    got = [np.full(plan.buffer_bytes(1, 0), H.POISON, dtype=np.uint8)]
+    host_exec.run_tiles(plan, bufs, got)
+    for q, e in zip(queries, plan.manifest(1, 0)):
+        full = oreshard.full_tensor(None, None, lay, q[0], q[1], lambda r, off, n: bufs[r][off:off + n])
+        want = np.ascontiguousarray(full[tuple(slice(l, h) for l, h in zip(q[2], q[3]))])
+        have = got[0][e.offset:e.offset + want.nbytes].view(want.dtype).reshape(want.shape)
+        assert np.array_equal(have, want), q
+    with pytest.raises(tpx.TpxError):
+        tpx.tpx_plan_query([[H.desc_of(e) for e in ent] for ent, _ in src], [(9999, 0, (0,), (1,))])
+
+
 def test_only_wanted_destination_ranks_are_built():
     src, dst = sequence(2), sequence(4)
     a = H.np_bufs(src_buffers(src, 3))

@@ -137,6 +137,28 @@ def test_rebuild_only_the_lost_ranks(cuda):
     torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("shift", [16, 48, 240])
+def test_rank_buffers_aligned_to_16_bytes_only(cuda, shift):
+    """The contract asks for 16-byte aligned rank buffers, not more: every buffer starts `shift` bytes into
+    its allocation (merge, multicast, fill and transposing tiles included)."""
+    for model, mix, a, b in ((WIDE, synth.MIX_GPT, Parallel(2, 2, 1), Parallel(4, 1, 2)),
+                             (ODD, ODD_MIX, Parallel(3, 1, 1), Parallel(4, 2, 1, w_transposed=1))):
+        src_cpu = H.make_src_bufs(model, a, 29, mix)
+        want = oreshard.reshard(model, a, b, H.np_bufs(src_cpu))
+        plan = plan_for(model, a, b)
+        src_gpu = []
+        for x in src_cpu:
+            t = G.alloc(x.numel() + 256, 0)
+            t[shift:shift + x.numel()] = x.cuda()
+            src_gpu.append(t[shift:shift + x.numel()])
+        dst_gpu = [G.alloc(plan.buffer_bytes(1, r) + 256, H.POISON)[shift:shift + plan.buffer_bytes(1, r)] for r in range(b.n_ranks)]
+        assert all(t.data_ptr() % 256 == shift for t in src_gpu + dst_gpu)
+        G.execute(plan, src_gpu, dst_bufs=dst_gpu)
+        torch.cuda.synchronize()
+        for r in range(b.n_ranks):
+            assert np.array_equal(dst_gpu[r].cpu().numpy(), want[r]), (shift, r)
+
+
 def test_execute_argument_errors(cuda):
     plan = plan_for(SMALL, Parallel(2, 1, 1), Parallel(1, 1, 1))
     src = [G.alloc(plan.buffer_bytes(0, r), 0) for r in range(2)]

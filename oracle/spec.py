@@ -82,6 +82,7 @@ class Parallel:
     qkv_layout: int = 0                         # 0 head-major [a,3,d,*]; 1 qkv-major [3,a,d,*]
     w_transposed: int = 0                       # 1: 2-D weights stored [in, out] instead of [out, in]
     shard_kinds: int = 0                        # bit k set: state kind k is sharded over the D replicas
+    layer_stage: Optional[tuple] = None         # stage of every layer (any map, e.g. interleaved chunks); overrides stage_first_layer
 
     @property
     def n_ranks(self) -> int:
@@ -125,7 +126,11 @@ def check(model: Model, par: Parallel) -> None:
     if model.n_heads % par.T or model.ffn % par.T or model.hidden % par.T:
         raise ValueError("heads / ffn / hidden not divisible by T")
     vocab_padded(model, par.T)
-    stage_bounds(model, par)
+    if par.layer_stage is not None:
+        if len(par.layer_stage) != model.n_layers or any(not 0 <= p < par.P for p in par.layer_stage):
+            raise ValueError("layer_stage needs one stage index below P per layer")
+    else:
+        stage_bounds(model, par)
     if par.shard_kinds >> len(model.state_elem_bytes):
         raise ValueError("shard_kinds names a state kind the model does not have")
 
@@ -181,11 +186,15 @@ def canonical(model: Model, par: Parallel, name: int):
 
 def stage_tensors(model: Model, par: Parallel, p: int):
     """(name, layer) of every parameter tensor held by stage p, in packing order."""
-    b = stage_bounds(model, par)
+    if par.layer_stage is not None:
+        layers = [layer for layer in range(model.n_layers) if par.layer_stage[layer] == p]
+    else:
+        b = stage_bounds(model, par)
+        layers = range(b[p], b[p + 1])
     out = []
     if p == 0:
         out += [(WORD_EMB, -1), (POS_EMB, -1)]
-    for layer in range(b[p], b[p + 1]):
+    for layer in layers:
         out += [(n, layer) for n in range(LN1_W, LN1_W + N_LAYER_NAMES)]
     if p == par.P - 1:
         out += [(LNF_W, -1), (LNF_B, -1)]

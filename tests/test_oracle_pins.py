@@ -317,6 +317,9 @@ PAIRS = [
     (Parallel(4, 2, 2, shard_kinds=2), Parallel(2, 2, 1)),
     (Parallel(2, 1, 1), Parallel(3, 2, 3, shard_kinds=3)),
     (Parallel(2, 1, 3, shard_kinds=1, qkv_layout=1), Parallel(1, 2, 5, shard_kinds=2, w_transposed=1)),
+    # any layer -> stage map: interleaved (virtual) pipeline chunks, and one stage left without layers
+    (Parallel(2, 2, 1, layer_stage=(0, 1, 0, 1)), Parallel(3, 2, 1)),
+    (Parallel(4, 1, 1), Parallel(2, 3, 2, layer_stage=(2, 0, 0, 2), shard_kinds=2)),
 ]
 
 
@@ -442,6 +445,29 @@ def test_pins_catch_a_plain_row_split_of_qkv_major(monkeypatch):
     monkeypatch.setattr(spec, "canonical", wrong)
     with pytest.raises((AssertionError, ValueError, IndexError)):
         test_tensor_parallel_forward_equivalence(Parallel(3, 1, 1, qkv_layout=1, w_transposed=0))
+
+
+def test_layer_stage_map_places_each_layer_once():
+    """phi for pipeline parallelism as an arbitrary map: every layer's tensors sit on exactly the named stage (every
+    tensor-parallel rank and replica of it), embeddings stay on stage 0 and the final LayerNorm on the last stage;
+    a contiguous map is the same configuration as the boundary list that describes it."""
+    model = SMALL
+    par = Parallel(2, 3, 2, layer_stage=(2, 0, 2, 1))
+    for rank in range(par.n_ranks):
+        t, p, d = spec.coords_of(par, rank)
+        entries, _ = spec.rank_manifest(model, par, rank)
+        layers = sorted({e.layer for e in entries if e.layer >= 0})
+        assert layers == [l for l in range(4) if par.layer_stage[l] == p]
+        names = {e.name for e in entries if e.layer < 0}
+        assert names == ({spec.WORD_EMB, spec.POS_EMB} if p == 0 else {spec.LNF_W, spec.LNF_B} if p == 2 else set())
+        offs = [e.offset for e in entries]
+        assert offs == sorted(offs)
+    a = [spec.rank_manifest(model, Parallel(2, 2, 1, layer_stage=(0, 0, 0, 1)), r) for r in range(4)]
+    b = [spec.rank_manifest(model, Parallel(2, 2, 1, stage_first_layer=(0, 3, 4)), r) for r in range(4)]
+    assert a == b
+    for bad in ((0, 1, 2), (0, 1, 3, 0), (0, -1, 0, 0)):
+        with pytest.raises(ValueError):
+            spec.rank_manifest(model, Parallel(2, 3, 1, layer_stage=bad), 0)
 
 
 def test_sharded_kind_hand_worked_golden():

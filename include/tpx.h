@@ -72,6 +72,10 @@ typedef struct {
                                         lost (section 5.3) and is never read.  Destination configuration: 0 = this rank
                                         is not to be built (say, it survived and keeps its state): no move is planned
                                         for it, its buffer is never written and may be NULL in tpx_execute. */
+  const uint32_t* layer_stage;       /* phi as an arbitrary map: n_layers stage indices (< P), e.g. the interleaved chunks
+                                        of a virtual pipeline; overrides stage_first_layer; NULL = not used.  A stage
+                                        holds its layers in ascending order; embeddings stay on stage 0, the final
+                                        LayerNorm on stage P-1. */
   uint32_t shard_kinds;              /* phi, sharded data parallelism: bit k set = state kind k is not replicated over
                                         the D replicas but cut between them: of each block its (t, p) share holds,
                                         replica d stores chunk d of ceil(n / D) rows along the block's outermost

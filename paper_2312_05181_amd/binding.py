@@ -46,7 +46,8 @@ class tpx_model(C.Structure):
 class tpx_parallel(C.Structure):
     _fields_ = [("T", C.c_uint32), ("P", C.c_uint32), ("D", C.c_uint32),
                 ("stage_first_layer", C.POINTER(C.c_uint32)), ("qkv_layout", C.c_uint32),
-                ("w_transposed", C.c_uint32), ("rank_alive", C.POINTER(C.c_uint8)), ("shard_kinds", C.c_uint32)]
+                ("w_transposed", C.c_uint32), ("rank_alive", C.POINTER(C.c_uint8)), ("layer_stage", C.POINTER(C.c_uint32)),
+                ("shard_kinds", C.c_uint32)]
 
 
 class tpx_entry(C.Structure):
@@ -140,7 +141,8 @@ def _model_struct(n_layers, hidden, n_heads, ffn, vocab_true, max_pos=1024, voca
     return m
 
 
-def _parallel_struct(T, P, D, stage_first_layer=None, qkv_layout=0, w_transposed=0, rank_alive=None, shard_kinds=0):
+def _parallel_struct(T, P, D, stage_first_layer=None, qkv_layout=0, w_transposed=0, rank_alive=None, shard_kinds=0,
+                     layer_stage=None):
     keep = []
     p = tpx_parallel(T, P, D)
     if stage_first_layer is not None:
@@ -152,6 +154,10 @@ def _parallel_struct(T, P, D, stage_first_layer=None, qkv_layout=0, w_transposed
         arr = (C.c_uint8 * len(rank_alive))(*[1 if a else 0 for a in rank_alive])
         keep.append(arr)
         p.rank_alive = C.cast(arr, C.POINTER(C.c_uint8))
+    if layer_stage is not None:
+        arr = (C.c_uint32 * len(layer_stage))(*layer_stage)
+        keep.append(arr)
+        p.layer_stage = C.cast(arr, C.POINTER(C.c_uint32))
     return p, keep
 
 
@@ -248,7 +254,7 @@ class Plan:
 
 def tpx_plan(model: dict, src: dict, dst: dict) -> Plan:
     """model: kwargs of the GPT-style model; src / dst: kwargs T, P, D[, stage_first_layer, qkv_layout,
-    w_transposed, rank_alive, shard_kinds]."""
+    w_transposed, rank_alive, shard_kinds, layer_stage (one stage index per layer)]."""
     m = _model_struct(**model)
     s, keep_s = _parallel_struct(**src)
     d, keep_d = _parallel_struct(**dst)

@@ -134,7 +134,10 @@ tpx_status build_side(const tpx_model& m, const tpx_parallel& par, Side& out) {
   out = Side{};
   out.tp_degree = par.T;
   std::vector<uint32_t> stage_first(par.P + 1);
-  if (par.stage_first_layer) {
+  if (par.layer_stage) {
+    for (uint32_t l = 0; l < m.n_layers; ++l)
+      if (par.layer_stage[l] >= par.P) return fail(TPX_ERR_BAD_STAGE_MAP, "layer_stage names a stage >= P");
+  } else if (par.stage_first_layer) {
     for (uint32_t p = 0; p <= par.P; ++p) stage_first[p] = par.stage_first_layer[p];
     if (stage_first[0] != 0 || stage_first[par.P] != m.n_layers)
       return fail(TPX_ERR_BAD_STAGE_MAP, "stage boundaries must start at 0 and end at n_layers");
@@ -159,8 +162,10 @@ tpx_status build_side(const tpx_model& m, const tpx_parallel& par, Side& out) {
     // the tensors of stage p in packing order
     std::vector<std::pair<uint32_t, int32_t>> held;
     if (p == 0) { held.push_back({WORD_EMB, -1}); held.push_back({POS_EMB, -1}); }
-    for (uint32_t l = stage_first[p]; l < stage_first[p + 1]; ++l)
+    for (uint32_t l = par.layer_stage ? 0 : stage_first[p]; l < (par.layer_stage ? m.n_layers : stage_first[p + 1]); ++l) {
+      if (par.layer_stage && par.layer_stage[l] != p) continue;
       for (uint32_t n = LN1_W; n <= FC2_B; ++n) held.push_back({n, int32_t(l)});
+    }
     if (p == par.P - 1) {
       held.push_back({LNF_W, -1});
       held.push_back({LNF_B, -1});

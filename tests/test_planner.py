@@ -26,7 +26,7 @@ def mk(model: Model) -> dict:
 
 def pk(par: Parallel, **extra) -> dict:
     d = dict(T=par.T, P=par.P, D=par.D, stage_first_layer=par.stage_first_layer, qkv_layout=par.qkv_layout,
-             w_transposed=par.w_transposed, shard_kinds=par.shard_kinds)
+             w_transposed=par.w_transposed, shard_kinds=par.shard_kinds, layer_stage=par.layer_stage)
     d.update(extra)
     return d
 
@@ -51,6 +51,7 @@ def _layout_cases():
     yield from ((H.CONFIGS[c][0], H.CONFIGS[c][1], H.CONFIGS[c][2]) for c in (1, 2, 3, 4, 5))
     yield H.GPT_1_3B, Parallel(4, 2, 2, shard_kinds=14), Parallel(2, 2, 4, shard_kinds=14, qkv_layout=1)   # sharded optimizer state
     yield H.TINY, Parallel(2, 1, 3, shard_kinds=7), Parallel(4, 2, 5, shard_kinds=2, w_transposed=1)
+    yield H.GPT_1_3B, Parallel(2, 4, 1, layer_stage=tuple((l // 3) % 4 for l in range(24))), Parallel(4, 2, 1)     # 2 chunks of 3 layers per stage
 
 
 @pytest.mark.parametrize("model,src,dst", list(_layout_cases()))
@@ -102,6 +103,10 @@ PAIRS = [
     (SMALL, SMALL_MIX, Parallel(2, 1, 3, shard_kinds=1, qkv_layout=1), Parallel(1, 2, 5, shard_kinds=2, w_transposed=1)),
     (ODD, ODD_MIX, Parallel(3, 1, 2, shard_kinds=2), Parallel(4, 1, 3, shard_kinds=3)),
     (WIDE, H.synth.MIX_GPT, Parallel(2, 2, 2, shard_kinds=14), Parallel(4, 1, 4, shard_kinds=14)),
+    # arbitrary layer -> stage maps (interleaved pipeline chunks; a stage without layers)
+    (SMALL, SMALL_MIX, Parallel(2, 2, 1, layer_stage=(0, 1, 0, 1)), Parallel(3, 2, 1)),
+    (SMALL, SMALL_MIX, Parallel(4, 1, 1), Parallel(2, 3, 2, layer_stage=(2, 0, 0, 2), shard_kinds=2)),
+    (SMALL, SMALL_MIX, Parallel(2, 2, 1, layer_stage=(1, 0, 1, 0)), Parallel(2, 4, 1, layer_stage=(3, 2, 1, 0))),
 ]
 
 
@@ -389,6 +394,9 @@ def test_sharded_kinds_have_no_replica_to_recover_from():
     with pytest.raises(tpx.TpxError) as ei:                                              # a kind the model lacks
         plan_for(SMALL, Parallel(2, 1, 2, shard_kinds=4), Parallel(1, 1, 1))
     assert ei.value.status == B.TPX_ERR_INVALID_ARG
+    with pytest.raises(tpx.TpxError) as ei:                                              # a layer on a stage that does not exist
+        tpx.tpx_plan(mk(SMALL), dict(T=2, P=2, D=1, layer_stage=(0, 1, 2, 0)), pk(Parallel(1, 1, 1)))
+    assert ei.value.status == B.TPX_ERR_BAD_STAGE_MAP
 
 
 # ---- error codes ----------------------------------------------------------------------------------

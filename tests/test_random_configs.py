@@ -45,8 +45,9 @@ def random_case(rng):
         else:
             stages = None
         shard = rng.randrange(1 << len(kinds)) if D > 1 and rng.random() < 0.5 else 0    # kinds cut over the replicas
-        return Parallel(T, P, D, stages, qkv_layout=rng.choice([0, 0, 1]), w_transposed=rng.choice([0, 0, 0, 1]),
-                        shard_kinds=shard)
+        lmap = tuple(rng.randrange(P) for _ in range(layers)) if rng.random() < 0.25 else None      # any layer -> stage map
+        return Parallel(T, P, D, stages if lmap is None else None, qkv_layout=rng.choice([0, 0, 1]),
+                        w_transposed=rng.choice([0, 0, 0, 1]), shard_kinds=shard, layer_stage=lmap)
     return model, par(), par()
 
 

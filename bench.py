@@ -73,6 +73,9 @@ SHARDED_PAIRS = {
     "gpt2.7b_(2,2,4)->(4,2,2)_sharded_opt": (_G27, _c(2, 2, 4, shard_kinds=14), _c(4, 2, 2, shard_kinds=14), "gpt", 31),
     "gpt1.3b_(4,1,4)->(2,2,2)_sharded_opt": (_G13, _c(4, 1, 4, shard_kinds=14), _c(2, 2, 2, shard_kinds=14), "gpt", 32),
 }
+# interleaved (virtual) pipeline: each of 4 stages holds 2 chunks of 3 layers; folded back to 2 plain stages
+SHARDED_PAIRS["gpt1.3b_(2,4,1)_interleaved->(4,2,1)"] = (_G13, _c(2, 4, 1, layer_stage=tuple((l // 3) % 4 for l in range(24))),
+                                                         _c(4, 2, 1), "gpt", 33)
 WORKLOADS.update(SHARDED_PAIRS)
 # failure recovery (section 5.3): one replica of every (t, p) share of (4,2,2) is lost; only those eight ranks are
 # rebuilt, each from its surviving replica
@@ -375,7 +378,7 @@ def cpu_baseline(args, model, src, dst, plan, src_bufs, dst_bufs, src_ptrs, dst_
                     model.get("max_pos", 1024), model.get("vocab_divisor", 0), tuple(model["state_elem_bytes"]))
     def opar(c):
         return spec.Parallel(c["T"], c["P"], c["D"], c.get("stage_first_layer"), c.get("qkv_layout", 0),
-                             c.get("w_transposed", 0), c.get("shard_kinds", 0))
+                             c.get("w_transposed", 0), c.get("shard_kinds", 0), c.get("layer_stage"))
     osrc, odst = opar(src), opar(dst)
     src_lay, dst_lay = oreshard.Layout(om, osrc), oreshard.Layout(om, odst)
     layers = min(args.cpu_layers, om.n_layers)

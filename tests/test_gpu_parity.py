@@ -345,8 +345,10 @@ def test_paper_reconfiguration_pairs(cuda, name):
     print("pair", name, flush=True)
     model = Model(mk_["n_layers"], mk_["hidden"], mk_["n_heads"], mk_["ffn"], mk_["vocab_true"], mk_.get("max_pos", 1024),
                   mk_.get("vocab_divisor", 0), tuple(mk_["state_elem_bytes"]))
-    src = Parallel(s_["T"], s_["P"], s_["D"], s_.get("stage_first_layer"), shard_kinds=s_.get("shard_kinds", 0))
-    dst = Parallel(d_["T"], d_["P"], d_["D"], d_.get("stage_first_layer"), shard_kinds=d_.get("shard_kinds", 0))
+    src = Parallel(s_["T"], s_["P"], s_["D"], s_.get("stage_first_layer"), shard_kinds=s_.get("shard_kinds", 0),
+                   layer_stage=s_.get("layer_stage"))
+    dst = Parallel(d_["T"], d_["P"], d_["D"], d_.get("stage_first_layer"), shard_kinds=d_.get("shard_kinds", 0),
+                   layer_stage=d_.get("layer_stage"))
     mix = synth.MIX_GPT
     plan = plan_for(model, src, dst)
     st = plan.stats()

@@ -110,7 +110,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(WORKLOADS) + [DATASET_WORKLOAD])
-    ap.add_argument("--cpu-layers", type=int, default=8, help="layers in the CPU oracle's sample (0 = skip)")
+    ap.add_argument("--cpu-layers", type=int, default=16, help="layers in the CPU oracle's sample (0 = skip)")
     ap.add_argument("--tile-bytes", type=int, default=0)
     ap.add_argument("--variant", type=int, default=-1)
     ap.add_argument("--streams", type=int, default=0)

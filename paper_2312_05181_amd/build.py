@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtpx.so")
-SELFTEST_SRC = os.path.join(ROOT, "examples", "reshard_selftest.cpp")
+SELFTEST_SRC = os.path.join(HERE, "examples", "reshard_selftest.cpp")
 SELFTEST = os.path.join(HERE, "tpx_selftest")
 HOST_SOURCES = ["layout.cpp", "planner.cpp", "dataset.cpp", "api.cpp"]
 HIP_SOURCES = ["kernels.hip"]

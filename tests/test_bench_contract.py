@@ -40,7 +40,7 @@ def test_bench_prints_one_json_line_with_the_contract_fields(cuda, workload):
 
 @pytest.mark.gpu
 def test_c_abi_without_python_or_torch(cuda):
-    """examples/reshard_selftest.cpp, built next to the library: plans, executes and checks a reshard through the
+    """paper_2312_05181_amd/examples/reshard_selftest.cpp, built next to the library: plans, executes and checks a reshard through the
     C ABI alone, with the system's HIP runtime."""
     exe = os.path.join(ROOT, "paper_2312_05181_amd", "tpx_selftest")
     assert os.path.exists(exe), "build it with python -m paper_2312_05181_amd.build"

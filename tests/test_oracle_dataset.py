@@ -96,3 +96,17 @@ def test_hand_worked_two_to_four_replicas_golden():
     assert ods.cursors_after(11, 4, 2, 1) == cur2
     parts, cur = ods.repartition([np.array(p, dtype=np.uint64) for p in two], cur2, 4, 4)
     assert [list(map(int, p)) for p in parts] == four and cur == cur4
+
+
+def test_pair_entries_move_like_their_ids():
+    """(offset, length) entries (section 5.2): a sample's two words travel together - column 0 of the
+    re-partitioned pairs is the re-partitioned id array, column 1 the same function of it as before."""
+    n, B = 1000, 48
+    G = synth.epoch_order(n, 4)
+    pairs = np.stack([G, G * np.uint64(7) + np.uint64(1)], axis=1)
+    cur = ods.cursors_after(n, B, 6, 5)
+    ids4, cur_ids = ods.repartition(ods.partition(G, B, 6), cur, B, 4)
+    pairs4, cur_pairs = ods.repartition(ods.partition(pairs, B, 6), cur, B, 4)
+    assert cur_ids == cur_pairs
+    for a, b in zip(ids4, pairs4):
+        assert np.array_equal(b[:, 0], a) and np.array_equal(b[:, 1], a * np.uint64(7) + np.uint64(1))

@@ -11,7 +11,9 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstring>
 #include <string>
+#include <vector>
 
 #include "tpx_internal.hpp"
 
@@ -363,21 +365,20 @@ KernelFn pick_kernel(uint64_t variant) {
 namespace tpx {
 
 tpx_status hip_upload_tables(void* workspace, const tpx_plan_s& plan, void* stream) {
+  // one host image of the whole workspace (header, flat boxes, prefix sums, coarse table, segments), one copy
   hipStream_t st = static_cast<hipStream_t>(stream);
   const WorkspaceLayout w = workspace_layout(plan);
-  uint8_t* base = static_cast<uint8_t*>(workspace);
+  std::vector<uint8_t> image(size_t(w.total), 0);
   const WorkspaceHeader h{plan.id, plan.flat.size(), plan.n_tiles, plan.segments.size()};
-  hipError_t e = hipMemcpyAsync(base + w.header_off, &h, sizeof(h), hipMemcpyHostToDevice, st);
-  if (e == hipSuccess)
-    e = hipMemcpyAsync(base + w.boxes_off, plan.flat.data(), plan.flat.size() * sizeof(FlatBox), hipMemcpyHostToDevice, st);
-  if (e == hipSuccess)
-    e = hipMemcpyAsync(base + w.first_off, plan.first_tile.data(), plan.first_tile.size() * sizeof(uint32_t), hipMemcpyHostToDevice, st);
-  if (e == hipSuccess)
-    e = hipMemcpyAsync(base + w.coarse_off, plan.coarse.data(), plan.coarse.size() * sizeof(uint32_t), hipMemcpyHostToDevice, st);
-  if (e == hipSuccess && !plan.segments.empty())
-    e = hipMemcpyAsync(base + w.seg_off, plan.segments.data(), plan.segments.size() * sizeof(tpx_segment), hipMemcpyHostToDevice, st);
+  std::memcpy(image.data() + w.header_off, &h, sizeof(h));
+  std::memcpy(image.data() + w.boxes_off, plan.flat.data(), plan.flat.size() * sizeof(FlatBox));
+  std::memcpy(image.data() + w.first_off, plan.first_tile.data(), plan.first_tile.size() * sizeof(uint32_t));
+  std::memcpy(image.data() + w.coarse_off, plan.coarse.data(), plan.coarse.size() * sizeof(uint32_t));
+  if (!plan.segments.empty())
+    std::memcpy(image.data() + w.seg_off, plan.segments.data(), plan.segments.size() * sizeof(tpx_segment));
+  hipError_t e = hipMemcpyAsync(workspace, image.data(), image.size(), hipMemcpyHostToDevice, st);
   if (e != hipSuccess) return hip_fail(e, "copying the plan tables to the workspace");
-  e = hipStreamSynchronize(st);
+  e = hipStreamSynchronize(st);  // the image must outlive the copy
   if (e != hipSuccess) return hip_fail(e, "waiting for the plan table copy");
   return TPX_OK;
 }

@@ -44,7 +44,8 @@ typedef enum {
   TPX_ERR_HIP = -5,           /* a HIP runtime call failed (message has the HIP error) */
   TPX_ERR_STALE_WORKSPACE = -6, /* the workspace does not (or no longer) hold this plan's tables */
   TPX_ERR_CURSOR = -7,        /* dataset cursors are not those of a whole number of steps */
-  TPX_ERR_UNRECOVERABLE = -8  /* some state has no surviving source holder */
+  TPX_ERR_UNRECOVERABLE = -8, /* some state has no surviving source holder */
+  TPX_ERR_TOO_LARGE = -9      /* the plan tables do not fit the static table array of tpx_execute_static */
 } tpx_status;
 
 #define TPX_MAX_RANKS 128u    /* buffers per side */
@@ -263,6 +264,22 @@ uint64_t   tpx_workspace_bytes(const tpx_plan_t*);
  * Errors: INVALID_ARG (NULL where a pointer is needed, misaligned pointer), HIP. */
 tpx_status tpx_execute(tpx_plan_t*, const void* const* src_bufs, void* const* dst_bufs,
                        void* workspace, void* hip_stream);
+
+/* tpx_execute for callers that cannot allocate device memory and so have no workspace to hand over: code
+ * whose launches are recorded into a HIP graph by someone else, tight serving loops, harnesses that forbid
+ * hipMalloc.  The plan tables live in a static device array inside the library instead, one array of
+ * TPX_STATIC_WORKSPACE_BYTES per GPU, held until the process ends; its address on the current device is
+ * looked up on the first call there.  The call allocates nothing on the device or through any library
+ * routine, takes the same src_bufs / dst_bufs (HOST arrays of DEVICE pointers, same alignment and NULL
+ * rules), launches the same kernel on `hip_stream` (which must belong to the current device) and gives the
+ * same bytes as tpx_execute.  When the array does not hold this plan's tables already (first call, or
+ * another plan ran in between), they are copied there on `hip_stream` and the call waits for that copy;
+ * otherwise it only launches.  All calls on one GPU share that GPU's array: calls that overlap there (other
+ * threads, or other streams while an earlier launch of a different plan is still running) race on it;
+ * calls on one stream, or separated by a wait, do not.  The plan is not modified.
+ * Errors: TOO_LARGE (tpx_workspace_bytes() > TPX_STATIC_WORKSPACE_BYTES: use tpx_execute), INVALID_ARG, HIP. */
+#define TPX_STATIC_WORKSPACE_BYTES (4u << 20)
+tpx_status tpx_execute_static(const tpx_plan_t*, const void* const* src_bufs, void* const* dst_bufs, void* hip_stream);
 
 /* Optional: copy the plan tables into `workspace` now (and wait for the copy), so that a following
  * tpx_execute with the same workspace only launches the kernel.  Required before a tpx_execute that is

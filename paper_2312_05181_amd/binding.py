@@ -23,7 +23,8 @@ _lib = C.CDLL(LIB_PATH)
 
 TPX_OK = 0
 TPX_ERR_INVALID_ARG, TPX_ERR_INDIVISIBLE, TPX_ERR_BAD_STAGE_MAP, TPX_ERR_OOM, TPX_ERR_HIP = -1, -2, -3, -4, -5
-TPX_ERR_STALE_WORKSPACE, TPX_ERR_CURSOR, TPX_ERR_UNRECOVERABLE = -6, -7, -8
+TPX_ERR_STALE_WORKSPACE, TPX_ERR_CURSOR, TPX_ERR_UNRECOVERABLE, TPX_ERR_TOO_LARGE = -6, -7, -8, -9
+TPX_STATIC_WORKSPACE_BYTES = 4 << 20
 TPX_MAX_RANKS = 128
 SIDE_SRC, SIDE_DST = 0, 1
 MODEL_TIED_HEAD = 1
@@ -112,6 +113,7 @@ _sigs = {
     "tpx_traffic": (C.c_int, [_P, C.POINTER(C.c_uint64)]),
     "tpx_workspace_bytes": (C.c_uint64, [_P]),
     "tpx_execute": (C.c_int, [_P, C.POINTER(_P), C.POINTER(_P), _P, _P]),
+    "tpx_execute_static": (C.c_int, [_P, C.POINTER(_P), C.POINTER(_P), _P]),
     "tpx_prepare": (C.c_int, [_P, _P, _P]),
     "tpx_workspace_forget": (None, [_P]),
     "tpx_workspace_check": (C.c_int, [_P, _P, _P]),
@@ -241,6 +243,14 @@ class Plan:
             raise TpxError(TPX_ERR_INVALID_ARG, "one pointer per rank buffer is required")
         _check(_lib.tpx_execute(self._h, src, dst, _P(workspace_ptr), _P(stream)))
 
+    def execute_static(self, src_ptrs: Sequence[int], dst_ptrs: Sequence[int], stream: int = 0) -> None:
+        """The same launch with the plan tables in the library's static device array: nothing is allocated."""
+        if len(src_ptrs) != self.num_buffers(SIDE_SRC) or len(dst_ptrs) != self.num_buffers(SIDE_DST):
+            raise TpxError(TPX_ERR_INVALID_ARG, "one pointer per rank buffer is required")
+        src = (_P * max(1, len(src_ptrs)))(*[_P(p) for p in src_ptrs])
+        dst = (_P * max(1, len(dst_ptrs)))(*[_P(p) for p in dst_ptrs])
+        _check(_lib.tpx_execute_static(self._h, src, dst, _P(stream)))
+
     def prepare(self, workspace_ptr: int, stream: int = 0) -> None:
         _check(_lib.tpx_prepare(self._h, _P(workspace_ptr), _P(stream)))
 
@@ -350,6 +360,10 @@ def tpx_plan_dataset(n_samples: int, global_batch: int, D_src: int, D_dst: int, 
 
 def tpx_execute(plan: Plan, src_ptrs, dst_ptrs, workspace_ptr, stream=0) -> None:
     plan.execute(src_ptrs, dst_ptrs, workspace_ptr, stream)
+
+
+def tpx_execute_static(plan: Plan, src_ptrs, dst_ptrs, stream=0) -> None:
+    plan.execute_static(src_ptrs, dst_ptrs, stream)
 
 
 def tpx_free(plan: Plan) -> None:

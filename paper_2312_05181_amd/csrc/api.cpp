@@ -36,6 +36,7 @@ tpx_status finish_plan(tpx_plan_s& p) {
   if (tpx_status st = tile_boxes(p, tuning().tile_bytes)) return st;
   if (tpx_status st = validate_tiles(p)) return st;
   finish_stats(p);
+  build_image(p);
   return TPX_OK;
 }
 }  // namespace
@@ -212,23 +213,37 @@ tpx_status tpx_prepare(tpx_plan_t* p, void* workspace, void* hip_stream) {
   return TPX_OK;
 }
 
-tpx_status tpx_execute(tpx_plan_t* p, const void* const* src_bufs, void* const* dst_bufs, void* workspace,
-                       void* hip_stream) {
-  if (!p || !src_bufs || !dst_bufs || !workspace) return fail(TPX_ERR_INVALID_ARG, "tpx_execute: NULL argument");
+static tpx_status check_rank_buffers(const tpx_plan_t* p, const void* const* src_bufs, void* const* dst_bufs, const char* who) {
+  const std::string w(who);
   const uint32_t ns = uint32_t(p->side[0].bytes.size()), nd = uint32_t(p->side[1].bytes.size());
   for (uint32_t r = 0; r < ns; ++r) {
     if (!src_bufs[r] && p->side[0].alive[r] && p->side[0].bytes[r])
-      return fail(TPX_ERR_INVALID_ARG, "tpx_execute: NULL source buffer for a live rank");
-    if (reinterpret_cast<uintptr_t>(src_bufs[r]) % 16) return fail(TPX_ERR_INVALID_ARG, "tpx_execute: source buffer not 16-byte aligned");
+      return fail(TPX_ERR_INVALID_ARG, w + ": NULL source buffer for a live rank");
+    if (reinterpret_cast<uintptr_t>(src_bufs[r]) % 16) return fail(TPX_ERR_INVALID_ARG, w + ": source buffer not 16-byte aligned");
   }
   for (uint32_t r = 0; r < nd; ++r) {
     if (!dst_bufs[r] && p->side[1].alive[r] && p->side[1].bytes[r])
-      return fail(TPX_ERR_INVALID_ARG, "tpx_execute: NULL destination buffer for a rank that is to be built");
-    if (reinterpret_cast<uintptr_t>(dst_bufs[r]) % 16) return fail(TPX_ERR_INVALID_ARG, "tpx_execute: destination buffer not 16-byte aligned");
+      return fail(TPX_ERR_INVALID_ARG, w + ": NULL destination buffer for a rank that is to be built");
+    if (reinterpret_cast<uintptr_t>(dst_bufs[r]) % 16) return fail(TPX_ERR_INVALID_ARG, w + ": destination buffer not 16-byte aligned");
   }
+  return TPX_OK;
+}
+
+tpx_status tpx_execute(tpx_plan_t* p, const void* const* src_bufs, void* const* dst_bufs, void* workspace,
+                       void* hip_stream) {
+  if (!p || !src_bufs || !dst_bufs || !workspace) return fail(TPX_ERR_INVALID_ARG, "tpx_execute: NULL argument");
+  if (tpx_status st = check_rank_buffers(p, src_bufs, dst_bufs, "tpx_execute")) return st;
   if (p->n_tiles == 0) return TPX_OK;
   if (tpx_status st = tpx_prepare(p, workspace, hip_stream)) return st;
-  return hip_launch_tiles(workspace, *p, src_bufs, ns, dst_bufs, nd, tuning().variant, hip_stream);
+  return hip_launch_tiles(workspace, *p, src_bufs, uint32_t(p->side[0].bytes.size()), dst_bufs,
+                          uint32_t(p->side[1].bytes.size()), tuning().variant, hip_stream);
+}
+
+tpx_status tpx_execute_static(const tpx_plan_t* p, const void* const* src_bufs, void* const* dst_bufs, void* hip_stream) {
+  if (!p || !src_bufs || !dst_bufs) return fail(TPX_ERR_INVALID_ARG, "tpx_execute_static: NULL argument");
+  if (tpx_status st = check_rank_buffers(p, src_bufs, dst_bufs, "tpx_execute_static")) return st;
+  return hip_execute_static(*p, src_bufs, uint32_t(p->side[0].bytes.size()), dst_bufs, uint32_t(p->side[1].bytes.size()),
+                            tuning().variant, hip_stream);
 }
 
 tpx_status tpx_workspace_check(const tpx_plan_t* p, const void* workspace, void* hip_stream) {

@@ -12,10 +12,17 @@
 
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
 #include "tpx_internal.hpp"
+
+// The plan tables of tpx_execute_static: one array per GPU the code object is loaded on, held until the
+// process ends.  In host code this name is only a handle for hipGetSymbolAddress; the device address is
+// looked up once per device (hip_execute_static) and that pointer is what copies and kernels get.  Host code
+// refers to it below, which is what makes the compiler keep it in the code object under a visible name.
+static __device__ __align__(256) uint8_t scratch[TPX_STATIC_WORKSPACE_BYTES];
 
 namespace {
 
@@ -365,20 +372,12 @@ KernelFn pick_kernel(uint64_t variant) {
 namespace tpx {
 
 tpx_status hip_upload_tables(void* workspace, const tpx_plan_s& plan, void* stream) {
-  // one host image of the whole workspace (header, flat boxes, prefix sums, coarse table, segments), one copy
+  // the plan keeps one host image of the whole workspace (header, flat boxes, prefix sums, coarse table,
+  // segments): one copy
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const WorkspaceLayout w = workspace_layout(plan);
-  std::vector<uint8_t> image(size_t(w.total), 0);
-  const WorkspaceHeader h{plan.id, plan.flat.size(), plan.n_tiles, plan.segments.size()};
-  std::memcpy(image.data() + w.header_off, &h, sizeof(h));
-  std::memcpy(image.data() + w.boxes_off, plan.flat.data(), plan.flat.size() * sizeof(FlatBox));
-  std::memcpy(image.data() + w.first_off, plan.first_tile.data(), plan.first_tile.size() * sizeof(uint32_t));
-  std::memcpy(image.data() + w.coarse_off, plan.coarse.data(), plan.coarse.size() * sizeof(uint32_t));
-  if (!plan.segments.empty())
-    std::memcpy(image.data() + w.seg_off, plan.segments.data(), plan.segments.size() * sizeof(tpx_segment));
-  hipError_t e = hipMemcpyAsync(workspace, image.data(), image.size(), hipMemcpyHostToDevice, st);
+  hipError_t e = hipMemcpyAsync(workspace, plan.image.data(), plan.image.size(), hipMemcpyHostToDevice, st);
   if (e != hipSuccess) return hip_fail(e, "copying the plan tables to the workspace");
-  e = hipStreamSynchronize(st);  // the image must outlive the copy
+  e = hipStreamSynchronize(st);  // the plan may be freed as soon as the caller likes
   if (e != hipSuccess) return hip_fail(e, "waiting for the plan table copy");
   return TPX_OK;
 }
@@ -420,6 +419,56 @@ tpx_status hip_launch_tiles(const void* workspace, const tpx_plan_s& plan, const
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(e, "launching the tile kernel");
   return TPX_OK;
+}
+
+namespace {
+// Per device: the address of that device's copy of `scratch` and the id of the plan whose tables the
+// library last put there (0 = none).  Nobody else knows the address, so the host-side record is exact.
+constexpr int kMaxDevices = 64;
+struct StaticTables {
+  void* ptr = nullptr;
+  uint64_t plan_id = 0;
+};
+StaticTables g_static[kMaxDevices];
+std::mutex g_static_mutex;
+}  // namespace
+
+tpx_status hip_execute_static(const tpx_plan_s& plan, const void* const* src, uint32_t n_src, void* const* dst,
+                              uint32_t n_dst, uint64_t variant, void* stream) {
+  if (plan.n_tiles == 0) return TPX_OK;
+  if (plan.image.size() > TPX_STATIC_WORKSPACE_BYTES)
+    return fail(TPX_ERR_TOO_LARGE, "tpx_execute_static: the plan tables take " + std::to_string(plan.image.size()) +
+                                       " bytes, more than TPX_STATIC_WORKSPACE_BYTES (" +
+                                       std::to_string(TPX_STATIC_WORKSPACE_BYTES) + "); use tpx_execute with a workspace");
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "tpx_execute_static: asking for the current device");
+  if (dev < 0 || dev >= kMaxDevices) return fail(TPX_ERR_INVALID_ARG, "tpx_execute_static: device index out of range");
+  if (stream) {
+    int sdev = -1;
+    e = hipStreamGetDevice(static_cast<hipStream_t>(stream), &sdev);
+    if (e != hipSuccess) return hip_fail(e, "tpx_execute_static: asking for the stream's device");
+    if (sdev != dev) return fail(TPX_ERR_INVALID_ARG, "tpx_execute_static: hip_stream belongs to another device than the current one");
+  }
+  void* tables = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    StaticTables& s = g_static[dev];
+    if (!s.ptr) {  // first call on this device: every GPU holds its own copy of the array at its own address
+      void* p = nullptr;
+      e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e != hipSuccess) return hip_fail(e, "tpx_execute_static: looking up the static table array");
+      if (!p) return fail(TPX_ERR_HIP, "tpx_execute_static: the static table array has no device address");
+      s.ptr = p;
+    }
+    if (s.plan_id != plan.id) {  // ordered on `stream` after whatever the caller's earlier launches there still read
+      s.plan_id = 0;
+      if (tpx_status st = hip_upload_tables(s.ptr, plan, stream)) return st;
+      s.plan_id = plan.id;
+    }
+    tables = s.ptr;
+  }
+  return hip_launch_tiles(tables, plan, src, n_src, dst, n_dst, variant, stream);
 }
 
 tpx_status hip_read_header(const void* workspace, void* stream, WorkspaceHeader* out) {

@@ -496,6 +496,18 @@ WorkspaceLayout workspace_layout(const tpx_plan_s& plan) {
   return w;
 }
 
+void build_image(tpx_plan_s& plan) {
+  const WorkspaceLayout w = workspace_layout(plan);
+  plan.image.assign(size_t(w.total), 0);
+  const WorkspaceHeader h{plan.id, plan.flat.size(), plan.n_tiles, plan.segments.size()};
+  std::memcpy(plan.image.data() + w.header_off, &h, sizeof(h));
+  if (!plan.flat.empty()) std::memcpy(plan.image.data() + w.boxes_off, plan.flat.data(), plan.flat.size() * sizeof(FlatBox));
+  std::memcpy(plan.image.data() + w.first_off, plan.first_tile.data(), plan.first_tile.size() * sizeof(uint32_t));
+  std::memcpy(plan.image.data() + w.coarse_off, plan.coarse.data(), plan.coarse.size() * sizeof(uint32_t));
+  if (!plan.segments.empty())
+    std::memcpy(plan.image.data() + w.seg_off, plan.segments.data(), plan.segments.size() * sizeof(tpx_segment));
+}
+
 void finish_stats(tpx_plan_s& plan) {
   tpx_stats_t& s = plan.stats;
   s.n_boxes = plan.boxes.size();

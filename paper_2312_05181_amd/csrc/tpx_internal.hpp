@@ -126,6 +126,7 @@ struct tpx_plan_s {
   bool uniform_tiles = true;    // every tile has the same number of destinations (same cost per byte)
   void* uploaded_ws = nullptr;  // device workspace that currently holds the tables
   uint64_t id = 0;              // process-unique, never 0: stamps the workspace header
+  std::vector<uint8_t> image;   // host image of the whole workspace (header and tables), what an upload copies
 };
 
 namespace tpx {
@@ -153,10 +154,15 @@ struct WorkspaceHeader {
   uint64_t plan_id, n_boxes, n_tiles, n_segments;
 };
 WorkspaceLayout workspace_layout(const tpx_plan_s& plan);
+void build_image(tpx_plan_s& plan);  // fills plan.image from id, flat, first_tile, coarse and segments
 tpx_status hip_upload_tables(void* workspace, const tpx_plan_s& plan, void* stream);
 tpx_status hip_launch_tiles(const void* workspace, const tpx_plan_s& plan, const void* const* src, uint32_t n_src,
                             void* const* dst, uint32_t n_dst, uint64_t variant, void* stream);
 tpx_status hip_probe_copy(void* dst, const void* src, uint64_t nbytes, void* stream);
 tpx_status hip_read_header(const void* workspace, void* stream, WorkspaceHeader* out);
+// Like hip_upload_tables + hip_launch_tiles with the tables in the library's own static device array of
+// TPX_STATIC_WORKSPACE_BYTES (one per GPU); allocates nothing.
+tpx_status hip_execute_static(const tpx_plan_s& plan, const void* const* src, uint32_t n_src, void* const* dst,
+                              uint32_t n_dst, uint64_t variant, void* stream);
 
 }  // namespace tpx

@@ -43,15 +43,6 @@ def _box(lo, hi) -> tuple:
     return tuple(slice(l, u) for l, u in zip(lo, hi))
 
 
-def holders(model: Model, par: Parallel, tid: int, kind: int):
-    """Every (rank, entry) of configuration `par` that stores a piece of state tensor (tid, kind)."""
-    out = []
-    for rank in range(par.n_ranks):
-        entries, _ = spec.rank_manifest(model, par, rank)
-        out += [(rank, e) for e in entries if e.tensor_id == tid and e.kind == kind]
-    return out
-
-
 class Layout:
     """All rank manifests of one configuration, indexed by (tensor id, kind).
 

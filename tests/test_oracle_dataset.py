@@ -110,3 +110,76 @@ def test_pair_entries_move_like_their_ids():
     assert cur_ids == cur_pairs
     for a, b in zip(ids4, pairs4):
         assert np.array_equal(b[:, 0], a) and np.array_equal(b[:, 1], a * np.uint64(7) + np.uint64(1))
+
+
+def cursors_by_counting(sizes, cursors, B, D2):
+    """New cursors derived without any notion of a step: the global positions the old replicas have consumed (the
+    first cursors[j] positions that belong to replica j), counted per replica of the new degree."""
+    n, D = sum(sizes), len(sizes)
+    b, b2 = B // D, B // D2
+    consumed = []
+    for j in range(D):
+        mine = [p for p in range(n) if (p % B) // b == j]
+        assert len(mine) == sizes[j]
+        consumed += mine[:cursors[j]]
+    return [sum(1 for p in consumed if (p % B) // b2 == j2) for j2 in range(D2)]
+
+
+@pytest.mark.parametrize("n,B,D,D2", [(100, 24, 6, 4), (101, 24, 4, 6), (53, 12, 2, 3), (53, 12, 3, 4), (7, 12, 6, 4),
+                                      (5, 8, 4, 2), (13, 8, 4, 2), (10, 8, 2, 4), (29, 12, 3, 6), (96, 24, 6, 4)])
+def test_new_cursors_equal_a_count_of_consumed_positions(n, B, D, D2):
+    G = synth.epoch_order(n, 11)
+    parts = ods.partition(G, B, D)
+    for s in range(-(-n // B) + 2):          # every step count up to and past the end of the epoch
+        cur = ods.cursors_after(n, B, D, s)
+        _, new_cur = ods.repartition(parts, cur, B, D2)
+        assert new_cur == cursors_by_counting([len(p) for p in parts], cur, B, D2), s
+
+
+def _ragged_cases():
+    path = os.path.join(os.path.dirname(__file__), "golden", "dataset_ragged_tails.txt")
+    lines = [l.split("#")[0].strip() for l in open(path)]
+    lines = [l for l in lines if l]
+    cases, i = [], 0
+    while i < len(lines):
+        n, D, D2 = (int(x) for x in lines[i].split())
+        rows = [[] if l == "-" else [int(x) for x in l.split()] for l in lines[i + 1:i + 1 + D + D2]]
+        i += 1 + D + D2
+        steps = []
+        while i < len(lines) and ":" in lines[i]:
+            s, a, b = lines[i].split(":")
+            steps.append((int(s), [int(x) for x in a.split()], [int(x) for x in b.split()]))
+            i += 1
+        cases.append((n, D, D2, rows[:D], rows[D:], steps))
+    return cases
+
+
+def test_hand_worked_ragged_tails_golden():
+    """Global batch 8: a tail shorter than a local batch, a tail spanning several partitions, fewer samples than a batch."""
+    cases = _ragged_cases()
+    assert [c[0] for c in cases] == [10, 13, 5]
+    for n, D, D2, old, new, steps in cases:
+        G = np.arange(n, dtype=np.uint64)
+        assert [list(map(int, p)) for p in ods.partition(G, 8, D)] == old
+        assert [list(map(int, p)) for p in ods.partition(G, 8, D2)] == new
+        for s, cur, cur2 in steps:
+            assert ods.cursors_after(n, 8, D, s) == cur and ods.cursors_after(n, 8, D2, s) == cur2
+            parts, got = ods.repartition([np.array(p, dtype=np.uint64) for p in old], cur, 8, D2)
+            assert [list(map(int, p)) for p in parts] == new and got == cur2, (n, s)
+            assert cursors_by_counting([len(p) for p in old], cur, 8, D2) == cur2
+
+
+def test_pins_catch_a_floor_instead_of_ceiling_at_the_epoch_end(monkeypatch):
+    """Planted mistake: taking floor(size / b) whole steps when partition 0 is exhausted loses the ragged last step."""
+    real = ods.steps_done
+
+    def wrong(sizes, cursors, B):
+        b = B // len(sizes)
+        if cursors[0] >= sizes[0]:
+            return sizes[0] // b
+        return real(sizes, cursors, B)
+    monkeypatch.setattr(ods, "steps_done", wrong)
+    with pytest.raises(AssertionError):
+        test_hand_worked_ragged_tails_golden()
+    monkeypatch.setattr(ods, "steps_done", real)
+    test_hand_worked_ragged_tails_golden()

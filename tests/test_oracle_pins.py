@@ -514,3 +514,160 @@ def test_pins_catch_a_dropped_paste(monkeypatch):
     monkeypatch.setattr(oreshard, "_box", wrong)
     with pytest.raises((AssertionError, ValueError)):
         test_reshard_matches_value_function(*PAIRS[0])
+
+
+# --------------------------------------------------------------------------
+# phi: which stage holds which layer when no map is given; the tied output layer's copy
+# --------------------------------------------------------------------------
+def _stage_rows(name):
+    """rows of "a b | x y | ..." fixtures: ([a, b], [[x, y], ...]) per line."""
+    out = []
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if line:
+                head, *groups = [[int(x) for x in g.split()] for g in line.split("|")]
+                out.append((head, groups))
+    return out
+
+
+def test_even_stage_default_places_the_hand_listed_layers():
+    """Without a stage map, stage p of P holds layers [p*L/P, (p+1)*L/P) - on every tensor-parallel rank and
+    every replica of it - and nothing of any other layer (hand-written lists, including the 2.7B-shape source)."""
+    cases = _stage_rows("even_stages.txt")
+    assert len(cases) == 4
+    for (L, P), stages in cases:
+        assert len(stages) == P
+        model = Model(n_layers=L, hidden=8, n_heads=2, ffn=8, vocab_true=8, max_pos=2, state_elem_bytes=(2, 4))
+        par = Parallel(2, P, 2)
+        for rank in range(par.n_ranks):
+            t, p, d = spec.coords_of(par, rank)
+            entries, _ = spec.rank_manifest(model, par, rank)
+            for kind in range(2):
+                layers = [e.layer for e in entries if e.kind == kind and e.layer >= 0]
+                assert layers == [l for l in stages[p] for _ in range(spec.N_LAYER_NAMES)], (L, P, rank)
+    with pytest.raises(ValueError):          # 4 layers cannot be dealt evenly to 3 stages
+        spec.rank_manifest(Model(n_layers=4, hidden=8, n_heads=2, ffn=8, vocab_true=8, max_pos=2), Parallel(1, 3, 1), 0)
+    # the 2.7B-shape workload's source configuration itself, (4,4,2): ranks of stage 2 hold layers 16..23
+    m3, s3 = H.CONFIGS[3][0], H.CONFIGS[3][1]
+    for rank in (spec.rank_of(s3, 0, 2, 0), spec.rank_of(s3, 3, 2, 1)):
+        assert sorted({e.layer for e in spec.rank_manifest(m3, s3, rank)[0] if e.layer >= 0}) == cases[1][1][2]
+
+
+def test_pins_catch_a_wrong_even_stage_default(monkeypatch):
+    """Planted mistakes in the default stage map: boundaries rounded the wrong way round, and stages in reverse."""
+    real = spec.stage_bounds
+
+    def shifted(model, par):
+        b = list(real(model, par))
+        if par.stage_first_layer is None and par.P > 1:
+            b[1] += 1                      # first stage one layer too long
+        return tuple(b)
+    monkeypatch.setattr(spec, "stage_bounds", shifted)
+    with pytest.raises(AssertionError):
+        test_even_stage_default_places_the_hand_listed_layers()
+    monkeypatch.setattr(spec, "stage_bounds", real)
+    real_tensors = spec.stage_tensors
+
+    def reversed_stages(model, par, p):
+        out = real_tensors(model, par, p)
+        if par.stage_first_layer is None and par.layer_stage is None:
+            glob = [x for x in out if x[1] < 0]
+            other = [x for x in real_tensors(model, par, par.P - 1 - p) if x[1] >= 0]
+            out = [g for g in glob if g[0] < spec.LNF_W] + other + [g for g in glob if g[0] >= spec.LNF_W]
+        return out
+    monkeypatch.setattr(spec, "stage_tensors", reversed_stages)
+    with pytest.raises(AssertionError):
+        test_even_stage_default_places_the_hand_listed_layers()
+    monkeypatch.setattr(spec, "stage_tensors", real_tensors)
+    test_even_stage_default_places_the_hand_listed_layers()
+
+
+TIED = Model(n_layers=2, hidden=8, n_heads=2, ffn=16, vocab_true=12, max_pos=3, state_elem_bytes=(4, 2), tied_head=True)
+TIED_MIX = ((4, "u11"), (2, "index"))
+
+
+def _tied_golden():
+    rows = []
+    with open(os.path.join(GOLDEN, "tied_head_p2.txt")) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if line:
+                rows.append([(x.rsplit("@", 1)[0], int(x.rsplit("@", 1)[1])) for x in line.split()])
+    return rows
+
+
+def test_tied_head_copy_sits_on_the_last_stage():
+    """With a tied output layer and P > 1 the last stage stores the word embeddings too, after the final LayerNorm,
+    cut over the tensor-parallel ranks exactly like stage 0's; with P = 1 there is one copy (hand-written lists)."""
+    stage0, stage1, single = _tied_golden()
+    names = [n for n, _ in spec.NAMES]
+    for T in (1, 2):
+        par = Parallel(T, 2, 1)
+        for t in range(T):
+            for p, want in ((0, stage0), (1, stage1)):
+                entries, _ = spec.rank_manifest(TIED, par, spec.rank_of(par, t, p, 0))
+                for kind in range(2):
+                    got = [(names[e.name], e.layer) for e in entries if e.kind == kind]
+                    assert got == want, (T, t, p, kind)
+            first = [e for e in spec.rank_manifest(TIED, par, spec.rank_of(par, t, 0, 0))[0] if e.name == spec.WORD_EMB]
+            last = [e for e in spec.rank_manifest(TIED, par, spec.rank_of(par, t, 1, 0))[0] if e.name == spec.WORD_EMB]
+            assert [(e.tensor_id, e.kind, e.full_shape, e.lo, e.hi, e.perm) for e in first] == \
+                   [(e.tensor_id, e.kind, e.full_shape, e.lo, e.hi, e.perm) for e in last]
+            assert first[0].lo[0] == t * 12 // T and first[0].hi[0] == (t + 1) * 12 // T
+    entries, _ = spec.rank_manifest(TIED, Parallel(1, 1, 1), 0)
+    assert [(names[e.name], e.layer) for e in entries if e.kind == 0] == single
+    # a model without the flag has no second copy
+    plain = Model(**{**TIED.__dict__, "tied_head": False})
+    assert [e.name for e in spec.rank_manifest(plain, Parallel(1, 2, 1), 1)[0]].count(spec.WORD_EMB) == 0
+
+
+def test_tied_head_copy_is_a_replica_and_is_dropped_or_made_by_a_reshard():
+    """The copy on the last stage holds the same bytes as stage 0's shard; reassembly accepts it as a replica and
+    rejects it when it differs; P = 2 -> 1 leaves one copy, P = 1 -> 2 writes the second copy with stage 0's bytes;
+    either way every tensor equals the value function at its place."""
+    a, b = Parallel(2, 2, 1), Parallel(1, 1, 1)
+    src = H.np_bufs(H.make_src_bufs(TIED, a, 13, TIED_MIX))
+    for t in range(2):
+        r0, r1 = spec.rank_of(a, t, 0, 0), spec.rank_of(a, t, 1, 0)
+        for kind in range(2):
+            e0 = [e for e in spec.rank_manifest(TIED, a, r0)[0] if e.name == spec.WORD_EMB and e.kind == kind][0]
+            e1 = [e for e in spec.rank_manifest(TIED, a, r1)[0] if e.name == spec.WORD_EMB and e.kind == kind][0]
+            n = 6 * 8 * e0.elem_bytes
+            assert np.array_equal(src[r0][e0.offset:e0.offset + n], src[r1][e1.offset:e1.offset + n])
+    one = oreshard.reshard(TIED, a, b, src)
+    want = H.np_bufs(H.closed_form_dst_bufs(TIED, a, b, 13, TIED_MIX))
+    assert np.array_equal(one[0], want[0])
+    back = oreshard.reshard(TIED, b, a, one)                 # P = 1 -> 2: the second copy is made
+    assert all(np.array_equal(x, y) for x, y in zip(back, H.np_bufs(H.closed_form_dst_bufs(TIED, b, a, 13, TIED_MIX))))
+    for x, y in zip(back, src):                              # and the round trip gives back every tensor byte
+        keep = y != H.SRC_GAP
+        assert np.array_equal(x[keep], y[keep])
+    # a copy that differs from stage 0's is not a replica
+    bad = [x.copy() for x in src]
+    r1 = spec.rank_of(a, 1, 1, 0)
+    e1 = [e for e in spec.rank_manifest(TIED, a, r1)[0] if e.name == spec.WORD_EMB and e.kind == 0][0]
+    bad[r1][e1.offset + 5] ^= 0x10
+    with pytest.raises(AssertionError):
+        oreshard.reshard(TIED, a, b, bad)
+
+
+def test_pins_catch_a_missing_or_misplaced_tied_copy(monkeypatch):
+    real = spec.stage_tensors
+
+    def no_copy(model, par, p):
+        return [x for i, x in enumerate(real(model, par, p)) if not (x[0] == spec.WORD_EMB and i > 0)]
+    monkeypatch.setattr(spec, "stage_tensors", no_copy)
+    with pytest.raises(AssertionError):
+        test_tied_head_copy_sits_on_the_last_stage()
+
+    def copy_everywhere(model, par, p):               # also on stages that are not the last, and when P == 1
+        out = real(model, par, p)
+        if model.tied_head and not (p == par.P - 1 and par.P > 1):
+            out = out + [(spec.WORD_EMB, -1)] if p > 0 or par.P == 1 else out
+        return out
+    monkeypatch.setattr(spec, "stage_tensors", copy_everywhere)
+    with pytest.raises(AssertionError):
+        test_tied_head_copy_sits_on_the_last_stage()
+    monkeypatch.setattr(spec, "stage_tensors", real)
+    test_tied_head_copy_sits_on_the_last_stage()

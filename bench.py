@@ -135,21 +135,18 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
     torch.cuda.set_device(0)
-    if args.tile_bytes:
-        tpx.tpx_set_option("tile_bytes", args.tile_bytes)
     if args.variant >= 0:
         tpx.tpx_set_option("variant", args.variant)
     if args.streams:
         tpx.tpx_set_option("streams", args.streams)
-    if args.share_reads:
-        tpx.tpx_set_option("share_reads", 1)
+    args.opts = dict(tile_bytes=args.tile_bytes, share_reads=int(args.share_reads))
 
     if args.workload == DATASET_WORKLOAD:
         return bench_dataset(args)
 
     model, src, dst, mixname, seed = WORKLOADS[args.workload]
     mix = synth.MIX_TINY if mixname == "tiny" else synth.MIX_GPT
-    plan = tpx.tpx_plan(model, src, dst)
+    plan = tpx.tpx_plan(model, src, dst, args.opts)
     stats = plan.stats()
     n_src, n_dst = plan.num_buffers(0), plan.num_buffers(1)
 
@@ -179,7 +176,7 @@ def main() -> int:
     state_bytes = stats["bytes_read"] + stats["bytes_written"]
 
     def step(ev0=None, ev1=None):
-        p = tpx.tpx_plan(model, src, dst)           # a1-a5: host planner
+        p = tpx.tpx_plan(model, src, dst, args.opts)   # a1-a5: host planner
         p.prepare(ws.data_ptr(), stream)            # tile table -> HBM
         if ev0 is not None:
             ev0.record()
@@ -288,7 +285,7 @@ def bench_dataset(args) -> int:
     b = B // D
     full, tail = n // B, n % B
     cursors = [min(full * b + max(0, min(b, tail - j * b)), c["steps_done"] * b) for j in range(D)]
-    plan = tpx.tpx_plan_dataset(n, B, D, D2, cursors)
+    plan = tpx.tpx_plan_dataset(n, B, D, D2, cursors, opts=args.opts)
     stats = plan.stats()
     G = synth.epoch_order(n, c["seed"])
     # replica j holds, step by step, entries [k*B + j*b, k*B + (j+1)*b) of the global order
@@ -304,7 +301,7 @@ def bench_dataset(args) -> int:
     state_bytes = stats["bytes_read"] + stats["bytes_written"]
 
     def step(e0=None, e1=None):
-        p = tpx.tpx_plan_dataset(n, B, D, D2, cursors)
+        p = tpx.tpx_plan_dataset(n, B, D, D2, cursors, opts=args.opts)
         p.prepare(ws.data_ptr(), stream)
         if e0 is not None:
             e0.record()

@@ -42,10 +42,11 @@ typedef enum {
   TPX_ERR_BAD_STAGE_MAP = -3, /* stage boundaries not ascending from 0 to n_layers */
   TPX_ERR_OOM = -4,           /* host allocation failed */
   TPX_ERR_HIP = -5,           /* a HIP runtime call failed (message has the HIP error) */
-  TPX_ERR_STALE_WORKSPACE = -6, /* the workspace does not (or no longer) hold this plan's tables */
+  TPX_ERR_MISALIGNED = -6,    /* a device pointer is not aligned as the call requires */
   TPX_ERR_CURSOR = -7,        /* dataset cursors are not those of a whole number of steps */
   TPX_ERR_UNRECOVERABLE = -8, /* some state has no surviving source holder */
-  TPX_ERR_TOO_LARGE = -9      /* the plan tables do not fit the static table array of tpx_execute_static */
+  TPX_ERR_STALE_WORKSPACE = -9, /* the workspace does not (or no longer) hold this plan's tables */
+  TPX_ERR_TOO_LARGE = -10     /* the plan tables do not fit the static table array of tpx_execute_static */
 } tpx_status;
 
 #define TPX_MAX_RANKS 128u    /* buffers per side */
@@ -175,15 +176,32 @@ typedef struct {
   uint64_t plan_ns;           /* host time spent in tpx_plan */
 } tpx_stats_t;
 
+/* Options of one plan; NULL wherever a tpx_plan_opts* is taken means all defaults (a zero field too).
+ *   tile_bytes     upper bound of bytes per tile, the unit of GPU work: a power of two, 4096 .. 4194304; default
+ *                  131072.  Small jobs use smaller tiles, down to 16384, so that the launch still has thousands of
+ *                  workgroups.
+ *   max_multicast  most replicas one move may be written to (1 .. 128; default 8; 1 = every replica is copied
+ *                  separately).
+ *   share_reads    0 (default): every destination rank reads from the holder section 6.5's locality rule picks for
+ *                  it (its own device first), which minimises bytes_cross_rank; 1: all ranks of a replica group
+ *                  read what the group's first rank reads, so a piece wanted by n replicas is read once and written
+ *                  n times - fewer bytes through memory when all buffers share one GPU. */
+typedef struct {
+  uint64_t tile_bytes;
+  uint32_t max_multicast;
+  uint32_t share_reads;
+} tpx_plan_opts;
+
 /* Plan the transformation of the model state of `model` from configuration src to dst (section 4.2,
  * algorithm 1: split, re-partition, merge).  Host only; all arguments are HOST pointers read during the
  * call (nothing is retained).  On success *out owns the plan until tpx_free().  The plan fixes the layout
  * of every rank buffer of both sides (tpx_buffer_bytes, tpx_manifest): rank (t, p, d) is buffer
  * t + T*(d + D*p); inside it one arena per state kind, each holding the stage's tensors in the order
  * embeddings, layers ascending (12 tensors each), final LayerNorm, 256-byte aligned.
- * Errors: INVALID_ARG (NULL, zero degree, > TPX_MAX_RANKS ranks, element size not 1/2/4/8),
- * INDIVISIBLE, BAD_STAGE_MAP, UNRECOVERABLE (src->rank_alive leaves a tensor without holder), OOM. */
-tpx_status tpx_plan(const tpx_model* model, const tpx_parallel* src, const tpx_parallel* dst, tpx_plan_t** out);
+ * Errors: INVALID_ARG (NULL, zero degree, > TPX_MAX_RANKS ranks, element size not 1/2/4/8, option out of
+ * range), INDIVISIBLE, BAD_STAGE_MAP, UNRECOVERABLE (src->rank_alive leaves a tensor without holder), OOM. */
+tpx_status tpx_plan(const tpx_model* model, const tpx_parallel* src, const tpx_parallel* dst,
+                    const tpx_plan_opts* opts, tpx_plan_t** out);
 
 /* A parallelizable tensor collection given explicitly (section 4.1, equation 1; section 5.1: the per-GPU
  * description a model parallelizer hands over): for every rank, the sub-tensors it stores.  sigma is the
@@ -192,7 +210,11 @@ tpx_status tpx_plan(const tpx_model* model, const tpx_parallel* src, const tpx_p
  * expert parallelism (phi groups whole expert tensors), sequence parallelism (sigma slices sample
  * tensors), sharded optimizer state (section 4.3).  Used fields of tpx_entry: tensor_id and kind (together
  * the identity of a state tensor), elem_bytes (1, 2, 4, 8), ndim (1..4), offset, full_shape, lo, hi, perm;
- * nbytes may be 0 (computed); name and layer are not interpreted. */
+ * nbytes may be 0 (computed); name and layer are not interpreted.  An offset of TPX_OFFSET_AUTO asks the
+ * library to place the entry itself: a rank's entries are then packed in list order, each at the next
+ * 256-byte boundary after the entry before it (tpx_manifest tells where); a rank's entries must all be
+ * placed that way or none. */
+#define TPX_OFFSET_AUTO UINT64_MAX
 typedef struct {
   uint32_t n_ranks;                 /* 1..TPX_MAX_RANKS */
   const uint32_t* n_entries;        /* n_ranks counts */
@@ -208,7 +230,23 @@ typedef struct {
  * ranks with identical manifests whose indices form an arithmetic progression are treated as replicas
  * (multicast moves).  Errors: INVALID_ARG (malformed entry, overlap, missing tensor, no tiling),
  * UNRECOVERABLE, OOM. */
-tpx_status tpx_plan_ptc(const tpx_ptc* src, const tpx_ptc* dst, tpx_plan_t** out);
+tpx_status tpx_plan_ptc(const tpx_ptc* src, const tpx_ptc* dst, const tpx_plan_opts* opts, tpx_plan_t** out);
+
+/* A range query on a stored collection (section 5.2: "/2/embedding/weight[:, 2:4]" selects [2, 4) on axis 1):
+ * the box [lo, hi) of state tensor (tensor_id, kind), in the full tensor's coordinates. */
+typedef struct {
+  uint32_t tensor_id, kind;
+  uint64_t lo[4], hi[4];
+} tpx_query;
+
+/* Plan the gathering of n_queries boxes of the collection src, from whichever ranks hold their pieces, into
+ * ONE destination buffer: box i is stored dense, row-major in the tensor's own axis order, at the next
+ * 256-byte boundary after box i-1 (tpx_manifest(plan, TPX_SIDE_DST, 0, i) gives its place,
+ * tpx_buffer_bytes(plan, TPX_SIDE_DST, 0) the size to allocate).  Element size and rank of each tensor are
+ * taken from src.  It is tpx_plan_ptc with a one-rank destination the library lays out.
+ * Errors: INVALID_ARG (a tensor that src does not have, lo >= hi, hi beyond the tensor), UNRECOVERABLE, OOM. */
+tpx_status tpx_plan_query(const tpx_ptc* src, uint32_t n_queries, const tpx_query* queries,
+                          const tpx_plan_opts* opts, tpx_plan_t** out);
 
 /* Plan the transformation of the dataset state (sections 2.2 and 5.2): per-replica sample-index arrays
  * of one epoch are re-partitioned from D_src to D_dst replicas with the global batch unchanged, so that
@@ -219,7 +257,7 @@ tpx_status tpx_plan_ptc(const tpx_ptc* src, const tpx_ptc* dst, tpx_plan_t** out
  * receives the equivalent positions.  Errors: INVALID_ARG, INDIVISIBLE (B % D), CURSOR. */
 tpx_status tpx_plan_dataset(uint64_t n_samples, uint32_t global_batch, uint32_t index_elem_bytes,
                             uint32_t D_src, uint32_t D_dst, const uint64_t* src_cursors,
-                            uint64_t* dst_cursors, tpx_plan_t** out);
+                            uint64_t* dst_cursors, const tpx_plan_opts* opts, tpx_plan_t** out);
 
 /* Queries (cheap, host only; the plan is not modified and nothing is allocated for the caller).
  * side: TPX_SIDE_SRC / TPX_SIDE_DST.  Out-of-range indices give 0 / INVALID_ARG.  tpx_manifest lists the
@@ -254,15 +292,19 @@ uint64_t   tpx_workspace_bytes(const tpx_plan_t*);
 /* Apply the plan (section 5.1, step 4): one kernel launch on `hip_stream` (a hipStream_t, NULL = the
  * default stream).  src_bufs / dst_bufs are HOST arrays of DEVICE pointers, one per rank of the side,
  * each at least tpx_buffer_bytes() long and 16-byte aligned (256 recommended); entries of lost source
- * ranks and of destination ranks that are not built (rank_alive) may be NULL.  workspace is a DEVICE pointer to tpx_workspace_bytes() bytes, 64-byte aligned.
- * Every tensor byte of every destination rank that is built is written exactly once; bytes between tensors are left untouched;
- * sources are only read and must not overlap destinations.  The call does not wait for the kernel.
- * The first call with a given workspace copies the plan tables into it and waits for that copy;
- * later calls with the same workspace reuse it, so the caller must not modify the workspace in
- * between (see tpx_workspace_forget()).  A plan may be executed any number of times; concurrent
- * executions of one plan must use the same, already filled workspace.
- * Errors: INVALID_ARG (NULL where a pointer is needed, misaligned pointer), HIP. */
-tpx_status tpx_execute(tpx_plan_t*, const void* const* src_bufs, void* const* dst_bufs,
+ * ranks and of destination ranks that are not built (rank_alive) may be NULL.  workspace is a DEVICE pointer
+ * to tpx_workspace_bytes() bytes, 64-byte aligned.  Every tensor byte of every destination rank that is
+ * built is written exactly once; bytes between tensors are left untouched; sources are only read and must
+ * not overlap destinations.  The call does not wait for the kernel.
+ * The library remembers, per workspace address, which plan's tables it last copied there.  When that is not
+ * this plan (first use, or another plan has used the workspace since), the call copies the tables on
+ * `hip_stream` and waits for the copy; otherwise it only launches.  So two plans may take turns on one
+ * workspace, and any number of threads may execute one plan (the plan is not modified).  What the library
+ * cannot see is the caller overwriting or freeing the workspace: tell it with tpx_workspace_forget().
+ * Should the tables be overwritten unnoticed, the launch moves nothing (see tpx_workspace_check()).
+ * Errors: INVALID_ARG (NULL where a pointer is needed), MISALIGNED (a rank buffer not 16-byte aligned, the
+ * workspace not 64-byte aligned), HIP. */
+tpx_status tpx_execute(const tpx_plan_t*, const void* const* src_bufs, void* const* dst_bufs,
                        void* workspace, void* hip_stream);
 
 /* tpx_execute for callers that cannot allocate device memory and so have no workspace to hand over: code
@@ -277,7 +319,8 @@ tpx_status tpx_execute(tpx_plan_t*, const void* const* src_bufs, void* const* ds
  * otherwise it only launches.  All calls on one GPU share that GPU's array: calls that overlap there (other
  * threads, or other streams while an earlier launch of a different plan is still running) race on it;
  * calls on one stream, or separated by a wait, do not.  The plan is not modified.
- * Errors: TOO_LARGE (tpx_workspace_bytes() > TPX_STATIC_WORKSPACE_BYTES: use tpx_execute), INVALID_ARG, HIP. */
+ * Errors: TOO_LARGE (tpx_workspace_bytes() > TPX_STATIC_WORKSPACE_BYTES: use tpx_execute), INVALID_ARG,
+ * MISALIGNED, HIP. */
 #define TPX_STATIC_WORKSPACE_BYTES (4u << 20)
 tpx_status tpx_execute_static(const tpx_plan_t*, const void* const* src_bufs, void* const* dst_bufs, void* hip_stream);
 
@@ -285,18 +328,20 @@ tpx_status tpx_execute_static(const tpx_plan_t*, const void* const* src_bufs, vo
  * tpx_execute with the same workspace only launches the kernel.  Required before a tpx_execute that is
  * recorded into a HIP graph (stream capture allows neither the wait nor a copy from pageable host memory):
  * prepare outside the capture, then capture the execute, which is then a single kernel node.
- * Errors: INVALID_ARG, HIP. */
-tpx_status tpx_prepare(tpx_plan_t*, void* workspace, void* hip_stream);
+ * Errors: INVALID_ARG, MISALIGNED, HIP. */
+tpx_status tpx_prepare(const tpx_plan_t*, void* workspace, void* hip_stream);
 
-/* Forget which workspace holds the plan tables (call after overwriting or freeing it). */
-void tpx_workspace_forget(tpx_plan_t*);
+/* Forget what the library believes about `workspace` (call after overwriting or freeing it): the next
+ * tpx_execute or tpx_prepare with that address copies the tables again.  NULL forgets every workspace. */
+void tpx_workspace_forget(const void* workspace);
 
 /* The tables start with a header stamped with an id unique to the plan, and the kernel compares it with
  * the plan it was launched for: a tpx_execute on a workspace that another plan's tables (or anything
  * else) have overwritten since the upload moves nothing instead of following foreign tables.  This call
  * tells the caller about it: it waits for `hip_stream`, reads the header back and returns
- * TPX_ERR_STALE_WORKSPACE unless it is this plan's.  Use it after tpx_execute when the workspace's
- * history is in doubt.  Errors: INVALID_ARG, HIP, STALE_WORKSPACE. */
+ * TPX_ERR_STALE_WORKSPACE unless it is this plan's (and then also forgets the workspace, so that the next
+ * execute copies the tables again).  Use it after tpx_execute when the workspace's history is in doubt.
+ * Errors: INVALID_ARG, HIP, STALE_WORKSPACE. */
 tpx_status tpx_workspace_check(const tpx_plan_t*, const void* workspace, void* hip_stream);
 
 /* Release a plan (NULL is allowed).  The caller must make sure no tpx_execute launch of it is still being
@@ -306,28 +351,20 @@ void tpx_free(tpx_plan_t*);
 /* Description of the last failure on the calling thread (never NULL; valid until that thread's next failure). */
 const char* tpx_last_error(void);
 
-/* Global tuning knobs, read by later tpx_plan / tpx_execute calls on any thread (each knob is read and written
- * atomically; a plan being made while a knob changes sees the old or the new value):
- *   "tile_bytes"  upper bound of bytes per tile (power of two, 4096 .. 4194304; default 131072); small jobs
- *                 use smaller tiles, down to 16384, so that the launch still has thousands of workgroups
+/* Process-wide knobs of the executor, for experiments with the kernel (each is read and written atomically by
+ * any thread; what a plan contains never depends on them):
  *   "variant"     kernel variant, 0 (default) = chosen from the tile size: 1024 threads per workgroup with eight
  *                 nontemporal 16-byte loads in flight per thread for 128 KiB tiles, smaller workgroups for
  *                 smaller tiles; other values are a bit field documented in the kernel source
  *   "streams"     tile order (1 .. 1024; default 4): workgroup b executes the (b / streams)-th tile of the
  *                 (b % streams)-th contiguous part of the plan, so concurrent workgroups touch `streams`
  *                 distant regions of the buffers
- *   "max_multicast"  most replicas one move may be written to (1 .. 128; default 8; 1 = every replica is
- *                 copied separately)
- *   "share_reads" 0 (default): every destination rank reads from the holder section 6.5's locality rule
- *                 picks for it (its own device first), which minimises bytes_cross_rank; 1: all ranks of a
- *                 replica group read what the group's first rank reads, so a piece wanted by n replicas is
- *                 read once and written n times - fewer bytes through memory when all buffers share one GPU
  * Errors: INVALID_ARG for an unknown key or a value out of range. */
 tpx_status tpx_set_option(const char* key, uint64_t value);
 
 /* Plain device-to-device copy of nbytes (multiple of 16, DEVICE pointers 16-byte aligned) by a simple
  * grid-stride kernel on hip_stream: the yardstick for achievable HBM copy bandwidth and the
- * calibration point for hardware traffic counters. */
+ * calibration point for hardware traffic counters.  Errors: INVALID_ARG, MISALIGNED, HIP. */
 tpx_status tpx_probe_copy(void* dst, const void* src, uint64_t nbytes, void* hip_stream);
 
 #ifdef __cplusplus

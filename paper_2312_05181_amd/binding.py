@@ -23,7 +23,8 @@ _lib = C.CDLL(LIB_PATH)
 
 TPX_OK = 0
 TPX_ERR_INVALID_ARG, TPX_ERR_INDIVISIBLE, TPX_ERR_BAD_STAGE_MAP, TPX_ERR_OOM, TPX_ERR_HIP = -1, -2, -3, -4, -5
-TPX_ERR_STALE_WORKSPACE, TPX_ERR_CURSOR, TPX_ERR_UNRECOVERABLE, TPX_ERR_TOO_LARGE = -6, -7, -8, -9
+TPX_ERR_MISALIGNED, TPX_ERR_CURSOR, TPX_ERR_UNRECOVERABLE, TPX_ERR_STALE_WORKSPACE, TPX_ERR_TOO_LARGE = -6, -7, -8, -9, -10
+TPX_OFFSET_AUTO = 2 ** 64 - 1
 TPX_STATIC_WORKSPACE_BYTES = 4 << 20
 TPX_MAX_RANKS = 128
 SIDE_SRC, SIDE_DST = 0, 1
@@ -85,6 +86,14 @@ class tpx_ptc(C.Structure):
                 ("rank_alive", C.POINTER(C.c_uint8))]
 
 
+class tpx_plan_opts(C.Structure):
+    _fields_ = [("tile_bytes", C.c_uint64), ("max_multicast", C.c_uint32), ("share_reads", C.c_uint32)]
+
+
+class tpx_query(C.Structure):
+    _fields_ = [("tensor_id", C.c_uint32), ("kind", C.c_uint32), ("lo", C.c_uint64 * 4), ("hi", C.c_uint64 * 4)]
+
+
 class tpx_stats_t(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in ("n_pieces", "n_boxes", "n_tiles", "bytes_read", "bytes_written",
                                           "bytes_fill", "bytes_cross_rank", "plan_ns")]
@@ -94,10 +103,14 @@ assert C.sizeof(tpx_tile) == 80
 
 _P = C.c_void_p
 _sigs = {
-    "tpx_plan": (C.c_int, [C.POINTER(tpx_model), C.POINTER(tpx_parallel), C.POINTER(tpx_parallel), C.POINTER(_P)]),
-    "tpx_plan_ptc": (C.c_int, [C.POINTER(tpx_ptc), C.POINTER(tpx_ptc), C.POINTER(_P)]),
+    "tpx_plan": (C.c_int, [C.POINTER(tpx_model), C.POINTER(tpx_parallel), C.POINTER(tpx_parallel),
+                           C.POINTER(tpx_plan_opts), C.POINTER(_P)]),
+    "tpx_plan_ptc": (C.c_int, [C.POINTER(tpx_ptc), C.POINTER(tpx_ptc), C.POINTER(tpx_plan_opts), C.POINTER(_P)]),
+    "tpx_plan_query": (C.c_int, [C.POINTER(tpx_ptc), C.c_uint32, C.POINTER(tpx_query), C.POINTER(tpx_plan_opts),
+                                 C.POINTER(_P)]),
     "tpx_plan_dataset": (C.c_int, [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32,
-                                   C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(_P)]),
+                                   C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(tpx_plan_opts),
+                                   C.POINTER(_P)]),
     "tpx_num_buffers": (C.c_uint32, [_P, C.c_int]),
     "tpx_buffer_bytes": (C.c_uint64, [_P, C.c_int, C.c_uint32]),
     "tpx_num_entries": (C.c_uint32, [_P, C.c_int, C.c_uint32]),
@@ -143,8 +156,26 @@ def _model_struct(n_layers, hidden, n_heads, ffn, vocab_true, max_pos=1024, voca
     return m
 
 
+def _opts_struct(opts) -> "C.POINTER(tpx_plan_opts)":
+    """opts: None or a dict with any of tile_bytes, max_multicast, share_reads."""
+    if not opts:
+        return None
+    unknown = set(opts) - {"tile_bytes", "max_multicast", "share_reads"}
+    if unknown:
+        raise TpxError(TPX_ERR_INVALID_ARG, f"unknown plan option {sorted(unknown)[0]}")
+    return C.pointer(tpx_plan_opts(int(opts.get("tile_bytes", 0)), int(opts.get("max_multicast", 0)),
+                                   int(opts.get("share_reads", 0))))
+
+
 def _parallel_struct(T, P, D, stage_first_layer=None, qkv_layout=0, w_transposed=0, rank_alive=None, shard_kinds=0,
-                     layer_stage=None):
+                     layer_stage=None, n_layers=None):
+    # the library reads exactly P+1 / n_layers / T*P*D elements behind these pointers: refuse shorter or longer lists here
+    if stage_first_layer is not None and len(stage_first_layer) != P + 1:
+        raise TpxError(TPX_ERR_INVALID_ARG, f"stage_first_layer needs P+1 = {P + 1} entries, got {len(stage_first_layer)}")
+    if rank_alive is not None and len(rank_alive) != T * P * D:
+        raise TpxError(TPX_ERR_INVALID_ARG, f"rank_alive needs T*P*D = {T * P * D} entries, got {len(rank_alive)}")
+    if layer_stage is not None and n_layers is not None and len(layer_stage) != n_layers:
+        raise TpxError(TPX_ERR_INVALID_ARG, f"layer_stage needs one entry per layer ({n_layers}), got {len(layer_stage)}")
     keep = []
     p = tpx_parallel(T, P, D)
     if stage_first_layer is not None:
@@ -254,39 +285,44 @@ class Plan:
     def prepare(self, workspace_ptr: int, stream: int = 0) -> None:
         _check(_lib.tpx_prepare(self._h, _P(workspace_ptr), _P(stream)))
 
-    def workspace_forget(self) -> None:
-        _lib.tpx_workspace_forget(self._h)
-
     def workspace_check(self, workspace_ptr: int, stream: int = 0) -> None:
         """Wait for the stream and raise TpxError(TPX_ERR_STALE_WORKSPACE) unless the workspace holds this plan."""
         _check(_lib.tpx_workspace_check(self._h, _P(workspace_ptr), _P(stream)))
 
 
-def tpx_plan(model: dict, src: dict, dst: dict) -> Plan:
+def tpx_plan(model: dict, src: dict, dst: dict, opts: Optional[dict] = None) -> Plan:
     """model: kwargs of the GPT-style model; src / dst: kwargs T, P, D[, stage_first_layer, qkv_layout,
-    w_transposed, rank_alive, shard_kinds, layer_stage (one stage index per layer)]."""
+    w_transposed, rank_alive, shard_kinds, layer_stage (one stage index per layer)]; opts: tile_bytes,
+    max_multicast, share_reads of this plan."""
     m = _model_struct(**model)
-    s, keep_s = _parallel_struct(**src)
-    d, keep_d = _parallel_struct(**dst)
+    s, keep_s = _parallel_struct(n_layers=m.n_layers, **src)
+    d, keep_d = _parallel_struct(n_layers=m.n_layers, **dst)
     h = _P()
-    _check(_lib.tpx_plan(C.byref(m), C.byref(s), C.byref(d), C.byref(h)))
+    _check(_lib.tpx_plan(C.byref(m), C.byref(s), C.byref(d), _opts_struct(opts), C.byref(h)))
     del keep_s, keep_d
     return Plan(h.value)
 
 
 def _ptc_struct(manifests, rank_bytes=None, rank_alive=None):
     """manifests: per rank, a list of objects with attributes tensor_id, kind, elem_bytes, offset, full_shape,
-    lo, hi, perm (synth.ShardDesc has them; name and layer are optional)."""
+    lo, hi, perm (synth.ShardDesc has them; name and layer are optional; offset None = TPX_OFFSET_AUTO)."""
     keep = []
     n = len(manifests)
+    if rank_bytes is not None and len(rank_bytes) != n:
+        raise TpxError(TPX_ERR_INVALID_ARG, f"rank_bytes needs one entry per rank ({n}), got {len(rank_bytes)}")
+    if rank_alive is not None and len(rank_alive) != n:
+        raise TpxError(TPX_ERR_INVALID_ARG, f"rank_alive needs one entry per rank ({n}), got {len(rank_alive)}")
     counts = (C.c_uint32 * max(1, n))(*[len(m) for m in manifests])
     ptrs = (C.POINTER(tpx_entry) * max(1, n))()
     for r, man in enumerate(manifests):
         arr = (tpx_entry * max(1, len(man)))()
         for i, d in enumerate(man):
             e = arr[i]
-            e.tensor_id, e.kind, e.elem_bytes, e.offset = d.tensor_id, d.kind, d.elem_bytes, d.offset
+            e.tensor_id, e.kind, e.elem_bytes = d.tensor_id, d.kind, d.elem_bytes
+            e.offset = TPX_OFFSET_AUTO if d.offset is None else d.offset
             e.ndim = len(d.full_shape)
+            if not (len(d.lo) == len(d.hi) == len(d.perm) == e.ndim <= 4):
+                raise TpxError(TPX_ERR_INVALID_ARG, "lo, hi, perm and full_shape must have the same length, at most 4")
             e.name, e.layer = getattr(d, "name", 0), getattr(d, "layer", -1)
             for k in range(e.ndim):
                 e.full_shape[k], e.lo[k], e.hi[k], e.perm[k] = d.full_shape[k], d.lo[k], d.hi[k], d.perm[k]
@@ -305,56 +341,46 @@ def _ptc_struct(manifests, rank_bytes=None, rank_alive=None):
     return c, keep
 
 
-def tpx_plan_ptc(src_manifests, dst_manifests, src_bytes=None, dst_bytes=None, src_alive=None, dst_alive=None) -> Plan:
+def tpx_plan_ptc(src_manifests, dst_manifests, src_bytes=None, dst_bytes=None, src_alive=None, dst_alive=None,
+                 opts: Optional[dict] = None) -> Plan:
     """Plan between two explicitly given collections (any sharding expressible as boxes of tensors).
     src_alive: 0 = that source rank is lost; dst_alive: 0 = that destination rank is not to be built."""
     s, keep_s = _ptc_struct(src_manifests, src_bytes, src_alive)
     d, keep_d = _ptc_struct(dst_manifests, dst_bytes, dst_alive)
     h = _P()
-    _check(_lib.tpx_plan_ptc(C.byref(s), C.byref(d), C.byref(h)))
+    _check(_lib.tpx_plan_ptc(C.byref(s), C.byref(d), _opts_struct(opts), C.byref(h)))
     del keep_s, keep_d
     return Plan(h.value)
 
 
-class _QueryEntry:
-    def __init__(self, like, lo, hi, offset):
-        self.tensor_id, self.kind, self.elem_bytes, self.full_shape = like.tensor_id, like.kind, like.elem_bytes, tuple(like.full_shape)
-        self.lo, self.hi, self.offset = tuple(lo), tuple(hi), offset
-        self.perm = tuple(range(len(self.full_shape)))      # dense, canonical axis order
-
-
-def tpx_plan_query(src_manifests, queries, src_bytes=None, src_alive=None) -> Plan:
+def tpx_plan_query(src_manifests, queries, src_bytes=None, src_alive=None, opts: Optional[dict] = None) -> Plan:
     """Range queries on a stored collection (paper section 5.2: "/2/embedding/weight[:, 2:4]"): queries is a list of
     (tensor_id, kind, lo, hi) boxes in the full tensors' coordinates; the plan gathers them, from whichever ranks
-    hold the pieces, into ONE destination buffer, each box dense row-major, one after the other at 256-byte
-    boundaries (plan.manifest(1, 0) gives the offsets).  Marshalling only: it is tpx_plan_ptc with a
-    one-rank destination."""
-    by_tensor = {}
-    for man in src_manifests:
-        for d in man:
-            by_tensor.setdefault((d.tensor_id, d.kind), d)
-    dst, off = [], 0
-    for tensor_id, kind, lo, hi in queries:
-        if (tensor_id, kind) not in by_tensor:
-            raise TpxError(TPX_ERR_INVALID_ARG, f"tensor {tensor_id} kind {kind} is not in the collection")
-        like = by_tensor[(tensor_id, kind)]
-        off = -(-off // 256) * 256
-        dst.append(_QueryEntry(like, lo, hi, off))
-        n = like.elem_bytes
-        for l, h in zip(lo, hi):
-            n *= h - l
-        off += n
-    return tpx_plan_ptc(src_manifests, [dst], src_bytes=src_bytes, src_alive=src_alive)
+    hold the pieces, into ONE destination buffer laid out by the library (plan.manifest(1, 0) gives the offsets,
+    plan.buffer_bytes(1, 0) the size)."""
+    s, keep_s = _ptc_struct(src_manifests, src_bytes, src_alive)
+    qs = (tpx_query * max(1, len(queries)))()
+    for q, (tensor_id, kind, lo, hi) in zip(qs, queries):
+        if not (len(lo) == len(hi) <= 4):
+            raise TpxError(TPX_ERR_INVALID_ARG, "a query's lo and hi must have the same length, at most 4")
+        q.tensor_id, q.kind = tensor_id, kind
+        for k in range(len(lo)):
+            q.lo[k], q.hi[k] = lo[k], hi[k]
+    h = _P()
+    _check(_lib.tpx_plan_query(C.byref(s), len(queries), qs, _opts_struct(opts), C.byref(h)))
+    del keep_s
+    return Plan(h.value)
 
 
 def tpx_plan_dataset(n_samples: int, global_batch: int, D_src: int, D_dst: int, src_cursors: Sequence[int],
-                     index_elem_bytes: int = 8) -> Plan:
+                     index_elem_bytes: int = 8, opts: Optional[dict] = None) -> Plan:
     if len(src_cursors) != D_src:
         raise TpxError(TPX_ERR_INVALID_ARG, "one cursor per source replica is required")
     cur = (C.c_uint64 * max(1, D_src))(*src_cursors)
     out = (C.c_uint64 * max(1, D_dst))()
     h = _P()
-    _check(_lib.tpx_plan_dataset(n_samples, global_batch, index_elem_bytes, D_src, D_dst, cur, out, C.byref(h)))
+    _check(_lib.tpx_plan_dataset(n_samples, global_batch, index_elem_bytes, D_src, D_dst, cur, out, _opts_struct(opts),
+                                 C.byref(h)))
     return Plan(h.value, [int(out[i]) for i in range(D_dst)])
 
 
@@ -368,6 +394,11 @@ def tpx_execute_static(plan: Plan, src_ptrs, dst_ptrs, stream=0) -> None:
 
 def tpx_free(plan: Plan) -> None:
     plan.close()
+
+
+def tpx_workspace_forget(workspace_ptr: int = 0) -> None:
+    """Tell the library that a workspace was overwritten or freed (0: all of them)."""
+    _lib.tpx_workspace_forget(_P(workspace_ptr))
 
 
 def tpx_set_option(key: str, value: int) -> None:

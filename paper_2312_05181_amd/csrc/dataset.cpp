@@ -43,21 +43,15 @@ tpx_status plan_dataset_moves(tpx_plan_s& plan, uint64_t n, uint32_t B, uint32_t
     for (uint32_t j = 0; j < deg; ++j) s.bytes[j] = (full * w + tail_part(tail, w, j)) * eb;
   }
 
-  // cursors: find the step count s with cursor_j = min(size_j, s*b) for all j (smallest such s)
-  const uint64_t size0 = full * b + tail_part(tail, b, 0);
-  uint64_t steps;
-  if (src_cursors[0] < size0) {
-    if (src_cursors[0] % b) return fail(TPX_ERR_CURSOR, "dataset: cursor of partition 0 is not at a step boundary");
-    steps = src_cursors[0] / b;
-  } else if (src_cursors[0] == size0) {
-    steps = (size0 + b - 1) / b;
-  } else {
-    return fail(TPX_ERR_CURSOR, "dataset: cursor of partition 0 is past its end");
-  }
+  // cursors: the job has done `steps` whole steps iff every replica has consumed min(its entries, steps * b).
+  // The furthest any replica has got, in local batches, is the only candidate; the ragged end counts as a step.
+  uint64_t steps = 0;
+  for (uint32_t j = 0; j < D; ++j) steps = std::max(steps, (src_cursors[j] + b - 1) / b);
   for (uint32_t j = 0; j < D; ++j) {
     const uint64_t size_j = full * b + tail_part(tail, b, j);
+    if (src_cursors[j] > size_j) return fail(TPX_ERR_CURSOR, "dataset: cursor of partition " + std::to_string(j) + " is past its end");
     if (src_cursors[j] != std::min(size_j, steps * b))
-      return fail(TPX_ERR_CURSOR, "dataset: cursor of partition " + std::to_string(j) + " does not match step " + std::to_string(steps));
+      return fail(TPX_ERR_CURSOR, "dataset: cursor of partition " + std::to_string(j) + " is not where " + std::to_string(steps) + " whole steps leave it");
   }
   dst_cursors.resize(Dn);
   for (uint32_t j = 0; j < Dn; ++j) dst_cursors[j] = std::min(full * bn + tail_part(tail, bn, j), steps * bn);

@@ -409,14 +409,17 @@ tpx_status hip_launch_tiles(const void* workspace, const tpx_plan_s& plan, const
   const uint32_t streams = plan.uniform_tiles && !(automatic && plan.needs_lds) ? uint32_t(std::max<uint64_t>(1, tuning().streams.load())) : 1;
   const uint32_t grid = uint32_t((plan.n_tiles + streams - 1) / streams * streams);
   KernelFn k = pick_kernel(variant);
-  hipLaunchKernelGGL(k, dim3(grid), dim3(threads_of(variant)), plan.needs_lds ? kLdsBytes : 0,
-                     static_cast<hipStream_t>(stream), reinterpret_cast<const WorkspaceHeader*>(base + w.header_off),
-                     plan.id, reinterpret_cast<const FlatBox*>(base + w.boxes_off),
-                     reinterpret_cast<const uint32_t*>(base + w.first_off),
-                     reinterpret_cast<const uint32_t*>(base + w.coarse_off),
-                     reinterpret_cast<const tpx_segment*>(base + w.seg_off), uint32_t(plan.flat.size()),
-                     uint32_t(plan.n_tiles), streams, pt);
-  const hipError_t e = hipGetLastError();
+  const WorkspaceHeader* a_header = reinterpret_cast<const WorkspaceHeader*>(base + w.header_off);
+  uint64_t a_id = plan.id;
+  const FlatBox* a_boxes = reinterpret_cast<const FlatBox*>(base + w.boxes_off);
+  const uint32_t* a_first = reinterpret_cast<const uint32_t*>(base + w.first_off);
+  const uint32_t* a_coarse = reinterpret_cast<const uint32_t*>(base + w.coarse_off);
+  const tpx_segment* a_segs = reinterpret_cast<const tpx_segment*>(base + w.seg_off);
+  uint32_t a_nboxes = uint32_t(plan.flat.size()), a_ntiles = uint32_t(plan.n_tiles), a_streams = streams;
+  void* args[] = {&a_header, &a_id, &a_boxes, &a_first, &a_coarse, &a_segs, &a_nboxes, &a_ntiles, &a_streams, &pt};
+  // the launch's own status, not the runtime's last-error slot, which other users of the runtime share
+  const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(k), dim3(grid), dim3(threads_of(variant)), args,
+                                       plan.needs_lds ? kLdsBytes : 0, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return hip_fail(e, "launching the tile kernel");
   return TPX_OK;
 }
@@ -484,9 +487,12 @@ tpx_status hip_probe_copy(void* dst, const void* src, uint64_t nbytes, void* str
   const uint64_t n = nbytes / 16;
   const uint64_t want = (n + kProbeThreads * 4 - 1) / (kProbeThreads * 4);
   const uint32_t grid = uint32_t(want < 256 * 16 ? want : 256 * 16);
-  hipLaunchKernelGGL(tpx_probe_copy_kernel, dim3(grid), dim3(kProbeThreads), 0, static_cast<hipStream_t>(stream),
-                     static_cast<v4u*>(dst), static_cast<const v4u*>(src), n);
-  const hipError_t e = hipGetLastError();
+  v4u* a_dst = static_cast<v4u*>(dst);
+  const v4u* a_src = static_cast<const v4u*>(src);
+  uint64_t a_n = n;
+  void* args[] = {&a_dst, &a_src, &a_n};
+  const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(tpx_probe_copy_kernel), dim3(grid), dim3(kProbeThreads),
+                                       args, 0, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return hip_fail(e, "launching the probe copy kernel");
   return TPX_OK;
 }

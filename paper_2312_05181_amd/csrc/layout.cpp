@@ -34,6 +34,23 @@ Tuning& tuning() {
   return t;
 }
 
+tpx_status resolve_opts(const tpx_plan_opts* in, tpx_plan_opts& out) {
+  out = tpx_plan_opts{131072, 8, 0};
+  if (!in) return TPX_OK;
+  if (in->tile_bytes) {
+    if (in->tile_bytes < 4096 || in->tile_bytes > 4194304 || (in->tile_bytes & (in->tile_bytes - 1)))
+      return fail(TPX_ERR_INVALID_ARG, "tile_bytes must be a power of two in [4096, 4194304]");
+    out.tile_bytes = in->tile_bytes;
+  }
+  if (in->max_multicast) {
+    if (in->max_multicast > 128) return fail(TPX_ERR_INVALID_ARG, "max_multicast must be in [1, 128]");
+    out.max_multicast = in->max_multicast;
+  }
+  if (in->share_reads > 1) return fail(TPX_ERR_INVALID_ARG, "share_reads must be 0 or 1");
+  out.share_reads = in->share_reads;
+  return TPX_OK;
+}
+
 const char* param_name(uint32_t name) { return name < N_NAMES ? kNames[name] : nullptr; }
 
 uint32_t tensor_id_of(uint32_t name, int32_t layer) {

@@ -166,7 +166,7 @@ tpx_status plan_model_moves(tpx_plan_s& plan) {
   };
   std::vector<Piece> pieces;
   std::vector<std::vector<int>> choice;
-  const uint64_t max_multicast = tuning().max_multicast, share_reads = tuning().share_reads;  // one reading per plan
+  const uint64_t max_multicast = plan.opts.max_multicast, share_reads = plan.opts.share_reads;
   auto unrecoverable = [&](const tpx_entry& sn) {
     return fail(TPX_ERR_UNRECOVERABLE, "no surviving holder of a piece of tensor " + std::to_string(sn.tensor_id) +
                                            (sn.name < N_NAMES && S.tp_degree ? std::string(" (") + param_name(sn.name) + ", layer " + std::to_string(sn.layer) + ")" : std::string()));

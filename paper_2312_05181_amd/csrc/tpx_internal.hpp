@@ -88,6 +88,7 @@ tpx_status find_groups(Side& side);   // builds groups from ranks (needed on the
 
 // Error reporting: sets the thread-local message and returns `st`.
 tpx_status fail(tpx_status st, const std::string& msg);
+tpx_status resolve_opts(const tpx_plan_opts* in, tpx_plan_opts& out);  // defaults for NULL / zero fields, range checks
 const char* last_error_cstr();
 
 const char* param_name(uint32_t name);
@@ -97,13 +98,10 @@ tpx_status check_model(const tpx_model& m);
 tpx_status sigma_of(const tpx_model& m, const tpx_parallel& par, uint32_t name, Sigma& out);
 tpx_status build_side(const tpx_model& m, const tpx_parallel& par, Side& out);
 
-// Process-wide knobs (tpx_set_option).  Atomic so that one thread may set them while others plan or execute:
-// each read sees the old or the new value, never a torn one.
+// Process-wide knobs of the executor (tpx_set_option).  Atomic so that one thread may set them while others
+// execute: each read sees the old or the new value, never a torn one.
 struct Tuning {
-  std::atomic<uint64_t> tile_bytes{131072};
   std::atomic<uint64_t> streams{4};        // tile order: workgroup b works on contiguous part b % streams of the plan
-  std::atomic<uint64_t> max_multicast{8};  // most destinations one move may be replicated to
-  std::atomic<uint64_t> share_reads{0};    // 1: all members of a replica group read what its first member reads
   std::atomic<uint64_t> variant{0};        // 0 = chosen from the tile size (1024 threads x 8 nontemporal loads for 128 KiB tiles)
 };
 Tuning& tuning();
@@ -124,7 +122,7 @@ struct tpx_plan_s {
   tpx_stats_t stats{};
   bool needs_lds = false;       // some tile is staged through LDS
   bool uniform_tiles = true;    // every tile has the same number of destinations (same cost per byte)
-  void* uploaded_ws = nullptr;  // device workspace that currently holds the tables
+  tpx_plan_opts opts{131072, 8, 0};  // the caller's options with defaults filled in
   uint64_t id = 0;              // process-unique, never 0: stamps the workspace header
   std::vector<uint8_t> image;   // host image of the whole workspace (header and tables), what an upload copies
 };

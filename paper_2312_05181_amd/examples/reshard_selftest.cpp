@@ -61,7 +61,7 @@ int main() {
   src.T = 3; src.P = 1; src.D = 2; src.shard_kinds = 4;           // the 8-byte kind is cut over the 2 replicas
   dst.T = 4; dst.P = 2; dst.D = 1; dst.qkv_layout = 1; dst.w_transposed = 1;
   tpx_plan_t* plan = nullptr;
-  TPX_OK_OR_DIE(tpx_plan(&m, &src, &dst, &plan));
+  TPX_OK_OR_DIE(tpx_plan(&m, &src, &dst, nullptr, &plan));
   tpx_stats_t st{};
   TPX_OK_OR_DIE(tpx_stats(plan, &st));
   std::printf("plan: %llu moves, %llu tiles, %llu bytes read, %llu written, %llu zero-filled\n", (unsigned long long)st.n_boxes,

@@ -9,7 +9,8 @@ A leaf is an object with
     "dtype":      "bfloat16" | "float16" | "float32" | "float64" | "int8" | "uint8" | "int16" | "int32" | "int64"
     "perm":       [..]          optional storage order (stored axis i = tensor axis perm[i])
 Every other object is a module; a tensor's identity is its path ("/transformer/h/0/attn/c_attn/weight"),
-the same on both sides.  Blocks are packed into the rank buffer in document order, 256-byte aligned.
+the same on both sides.  Where a block sits in its rank buffer is left to the library (offset None: it packs
+a rank's blocks in document order; the plan's manifest tells where).
 """
 from __future__ import annotations
 
@@ -21,7 +22,6 @@ Block = namedtuple("Block", "tensor_id kind elem_bytes offset full_shape lo hi p
 
 _BYTES = {"bfloat16": 2, "float16": 2, "float32": 4, "float64": 8, "int8": 1, "uint8": 1, "int16": 2, "int32": 4,
           "int64": 8}
-ALIGN = 256
 
 
 def _leaves(node, path=""):
@@ -38,33 +38,25 @@ def _leaves(node, path=""):
 
 
 def manifests_from_json(src_text: str, dst_text: str):
-    """-> (src_manifests, dst_manifests, src_bytes, dst_bytes, names); names[tensor_id] = path."""
+    """-> (src_manifests, dst_manifests, names); names[tensor_id] = path.  The manifests are what tpx_plan_ptc takes."""
     docs = [json.loads(src_text), json.loads(dst_text)]
     for d in docs:
         if not isinstance(d, list):
             raise ValueError("top level must be a list with one object per GPU")
     names = sorted({p for d in docs for gpu in d for p, _ in _leaves(gpu)})
     ids = {p: i for i, p in enumerate(names)}
-    out, sizes = [], []
+    out = []
     for d in docs:
-        mans, nbytes = [], []
+        mans = []
         for gpu in d:
-            off, blocks = 0, []
+            blocks = []
             for path, leaf in _leaves(gpu):
                 full = tuple(int(x) for x in leaf["full_shape"])
                 lo = tuple(int(x) for x in leaf.get("offset", [0] * len(full)))
                 shape = tuple(int(x) for x in leaf.get("shape", full))
                 hi = tuple(a + b for a, b in zip(lo, shape))
                 perm = tuple(int(x) for x in leaf.get("perm", range(len(full))))
-                eb = _BYTES[leaf.get("dtype", "float32")]
-                off = -(-off // ALIGN) * ALIGN
-                blocks.append(Block(ids[path], 0, eb, off, full, lo, hi, perm, 0, -1, path))
-                n = eb
-                for s in shape:
-                    n *= s
-                off += n
+                blocks.append(Block(ids[path], 0, _BYTES[leaf.get("dtype", "float32")], None, full, lo, hi, perm, 0, -1, path))
             mans.append(blocks)
-            nbytes.append(-(-off // ALIGN) * ALIGN)
         out.append(mans)
-        sizes.append(nbytes)
-    return out[0], out[1], sizes[0], sizes[1], names
+    return out[0], out[1], names

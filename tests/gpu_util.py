@@ -21,6 +21,7 @@ def execute(plan, src_bufs, dst_bufs=None, workspace=None, poison=True):
         dst_bufs = [alloc(plan.buffer_bytes(1, r), H.POISON if poison else None) for r in range(plan.num_buffers(1))]
     if workspace is None:
         workspace = alloc(plan.workspace_bytes())
+        tpx.tpx_workspace_forget(workspace.data_ptr())   # fresh memory: whatever the library once copied to this address is gone
     stream = torch.cuda.current_stream().cuda_stream
     tpx.tpx_execute(plan, [b.data_ptr() if b.numel() else 0 for b in src_bufs],
                     [b.data_ptr() if b.numel() else 0 for b in dst_bufs], workspace.data_ptr(), stream)

@@ -68,9 +68,10 @@ static tpx_parallel par(uint32_t T, uint32_t P, uint32_t D, const uint32_t* stag
   return p;
 }
 
-static void plan_and_walk(const tpx_model& m, const tpx_parallel& a, const tpx_parallel& b, uint64_t stride) {
+static void plan_and_walk(const tpx_model& m, const tpx_parallel& a, const tpx_parallel& b, uint64_t stride,
+                          const tpx_plan_opts* opts = nullptr) {
   tpx_plan_t* p = nullptr;
-  CHECK(tpx_plan(&m, &a, &b, &p) == TPX_OK);
+  CHECK(tpx_plan(&m, &a, &b, opts, &p) == TPX_OK);
   if (p) { walk(p, stride); tpx_free(p); }
 }
 
@@ -90,35 +91,37 @@ int main() {
     a.shard_kinds = 14; b.shard_kinds = 6; c.shard_kinds = 15;
     plan_and_walk(model(4, 24, 12, 48, 36, 0, 4), a, b, 1);
     plan_and_walk(model(4, 24, 12, 48, 36, 0, 4), b, c, 1);
-    CHECK(tpx_set_option("share_reads", 1) == TPX_OK);
-    plan_and_walk(model(4, 24, 12, 48, 36, 0, 4), c, a, 1);
-    plan_and_walk(model(24, 2048, 16, 8192, 50304, 0, 4), par(4, 2, 2), par(4, 2, 8), 19);
-    CHECK(tpx_set_option("share_reads", 0) == TPX_OK);
+    const tpx_plan_opts shared{0, 0, 1};
+    plan_and_walk(model(4, 24, 12, 48, 36, 0, 4), c, a, 1, &shared);
+    plan_and_walk(model(24, 2048, 16, 8192, 50304, 0, 4), par(4, 2, 2), par(4, 2, 8), 19, &shared);
     tpx_parallel bad = par(2, 1, 2);
     bad.shard_kinds = 16;
     tpx_plan_t* p = nullptr;
-    CHECK(tpx_plan(&(const tpx_model&)model(4, 24, 12, 48, 36, 0, 4), &bad, &a, &p) == TPX_ERR_INVALID_ARG);
+    CHECK(tpx_plan(&(const tpx_model&)model(4, 24, 12, 48, 36, 0, 4), &bad, &a, nullptr, &p) == TPX_ERR_INVALID_ARG);
+    const tpx_plan_opts odd_tile{5000, 0, 0}, wide{0, 129, 0}, twice{0, 0, 2};
+    for (const tpx_plan_opts* o : {&odd_tile, &wide, &twice})
+      CHECK(tpx_plan(&(const tpx_model&)model(4, 24, 12, 48, 36, 0, 4), &a, &b, o, &p) == TPX_ERR_INVALID_ARG);
+    CHECK(tpx_set_option("tile_bytes", 4096) == TPX_ERR_INVALID_ARG);   // a plan option, not a process-wide knob
   }
   const uint8_t alive[8] = {0, 0, 1, 1, 1, 1, 0, 0};
   plan_and_walk(model(4, 24, 12, 48, 36, 0, 4), par(2, 2, 2, nullptr, 0, 0, alive), par(2, 1, 1), 1);
   for (uint64_t tb : {4096ull, 65536ull, 4194304ull}) {
-    CHECK(tpx_set_option("tile_bytes", tb) == TPX_OK);
-    plan_and_walk(model(2, 256, 4, 1024, 1024, 0, 3), par(2, 1, 1), par(4, 2, 1, nullptr, 1, 1), 1);
+    const tpx_plan_opts o{tb, 3, 0};
+    plan_and_walk(model(2, 256, 4, 1024, 1024, 0, 3), par(2, 1, 1), par(4, 2, 1, nullptr, 1, 1), 1, &o);
   }
-  CHECK(tpx_set_option("tile_bytes", 131072) == TPX_OK);
   // dataset plans
   {
     const uint64_t cur[6] = {128 * 65000ull, 128 * 65000ull, 128 * 65000ull, 128 * 65000ull, 128 * 65000ull, 128 * 65000ull};
     uint64_t out[4];
     tpx_plan_t* p = nullptr;
-    CHECK(tpx_plan_dataset(100000000ull, 768, 8, 6, 4, cur, out, &p) == TPX_OK);
+    CHECK(tpx_plan_dataset(100000000ull, 768, 8, 6, 4, cur, out, nullptr, &p) == TPX_OK);
     if (p) { CHECK(out[0] == 192 * 65000ull); walk(p, 3); tpx_free(p); }
     const uint64_t zero[3] = {0, 0, 0};
-    CHECK(tpx_plan_dataset(0, 12, 8, 3, 2, zero, out, &p) == TPX_OK);
+    CHECK(tpx_plan_dataset(0, 12, 8, 3, 2, zero, out, nullptr, &p) == TPX_OK);
     if (p) { CHECK(tpx_num_tiles(p) == 0); tpx_free(p); }
     const uint64_t bad[3] = {1, 0, 0};
-    CHECK(tpx_plan_dataset(100, 12, 8, 3, 2, bad, out, &p) == TPX_ERR_CURSOR);
-    CHECK(tpx_plan_dataset(100, 13, 8, 3, 2, zero, out, &p) == TPX_ERR_INDIVISIBLE);
+    CHECK(tpx_plan_dataset(100, 12, 8, 3, 2, bad, out, nullptr, &p) == TPX_ERR_CURSOR);
+    CHECK(tpx_plan_dataset(100, 13, 8, 3, 2, zero, out, nullptr, &p) == TPX_ERR_INDIVISIBLE);
   }
   // explicit collection: a flat optimizer state in uneven chunks, 3 -> 4 ranks, plus errors
   {
@@ -135,35 +138,59 @@ int main() {
     const tpx_entry* dp[4] = {&d[0], &d[1], &d[2], &d[3]};
     tpx_ptc a{3, ones, sp, nullptr, nullptr}, b{4, ones, dp, nullptr, nullptr};
     tpx_plan_t* p = nullptr;
-    CHECK(tpx_plan_ptc(&a, &b, &p) == TPX_OK);
+    CHECK(tpx_plan_ptc(&a, &b, nullptr, &p) == TPX_OK);
     if (p) { walk(p, 1); tpx_free(p); }
     tpx_ptc half{2, ones, sp, nullptr, nullptr};
-    CHECK(tpx_plan_ptc(&half, &b, &p) == TPX_ERR_INVALID_ARG);
+    CHECK(tpx_plan_ptc(&half, &b, nullptr, &p) == TPX_ERR_INVALID_ARG);
     const uint8_t dead[3] = {1, 0, 1};
     tpx_ptc lost{3, ones, sp, nullptr, dead};
-    CHECK(tpx_plan_ptc(&lost, &b, &p) == TPX_ERR_UNRECOVERABLE);
+    CHECK(tpx_plan_ptc(&lost, &b, nullptr, &p) == TPX_ERR_UNRECOVERABLE);
+    // a range query over the three chunks, and offsets left to the library
+    const tpx_query qs[2] = {{7, 1, {30000, 0, 0, 0}, {70000, 0, 0, 0}}, {7, 1, {5, 0, 0, 0}, {6, 0, 0, 0}}};
+    CHECK(tpx_plan_query(&a, 2, qs, nullptr, &p) == TPX_OK);
+    if (p) {
+      tpx_entry e{};
+      CHECK(tpx_num_buffers(p, TPX_SIDE_DST) == 1 && tpx_num_entries(p, TPX_SIDE_DST, 0) == 2);
+      CHECK(tpx_manifest(p, TPX_SIDE_DST, 0, 1, &e) == TPX_OK && e.offset == 160000 && e.nbytes == 4);
+      CHECK(tpx_buffer_bytes(p, TPX_SIDE_DST, 0) == 160256);
+      walk(p, 1);
+      tpx_free(p);
+      p = nullptr;
+    }
+    const tpx_query nope{8, 1, {0, 0, 0, 0}, {1, 0, 0, 0}}, beyond{7, 1, {0, 0, 0, 0}, {n + 1, 0, 0, 0}};
+    CHECK(tpx_plan_query(&a, 1, &nope, nullptr, &p) == TPX_ERR_INVALID_ARG);
+    CHECK(tpx_plan_query(&a, 1, &beyond, nullptr, &p) == TPX_ERR_INVALID_ARG);
+    for (tpx_entry& e : d) e.offset = TPX_OFFSET_AUTO;
+    CHECK(tpx_plan_ptc(&a, &b, nullptr, &p) == TPX_OK);
+    if (p) { walk(p, 1); tpx_free(p); p = nullptr; }
     s[1].perm[0] = 3;
-    CHECK(tpx_plan_ptc(&a, &b, &p) == TPX_ERR_INVALID_ARG);
+    CHECK(tpx_plan_ptc(&a, &b, nullptr, &p) == TPX_ERR_INVALID_ARG);
   }
   // error paths of the model planner
   {
     tpx_plan_t* p = nullptr;
     tpx_model m = model(4, 24, 12, 48, 36, 0, 4);
     tpx_parallel one = par(1, 1, 1), five = par(5, 1, 1), three = par(1, 3, 1), big = par(8, 8, 4);
-    CHECK(tpx_plan(&m, &five, &one, &p) == TPX_ERR_INDIVISIBLE);
-    CHECK(tpx_plan(&m, &three, &one, &p) == TPX_ERR_INDIVISIBLE);
-    CHECK(tpx_plan(&m, &big, &one, &p) == TPX_ERR_INVALID_ARG);
+    CHECK(tpx_plan(&m, &five, &one, nullptr, &p) == TPX_ERR_INDIVISIBLE);
+    CHECK(tpx_plan(&m, &three, &one, nullptr, &p) == TPX_ERR_INDIVISIBLE);
+    CHECK(tpx_plan(&m, &big, &one, nullptr, &p) == TPX_ERR_INVALID_ARG);
     const uint32_t bad[3] = {0, 3, 2};
     tpx_parallel bs = par(1, 2, 1, bad);
-    CHECK(tpx_plan(&m, &bs, &one, &p) == TPX_ERR_BAD_STAGE_MAP);
-    CHECK(tpx_plan(nullptr, &one, &one, &p) == TPX_ERR_INVALID_ARG);
+    CHECK(tpx_plan(&m, &bs, &one, nullptr, &p) == TPX_ERR_BAD_STAGE_MAP);
+    CHECK(tpx_plan(nullptr, &one, &one, nullptr, &p) == TPX_ERR_INVALID_ARG);
     CHECK(p == nullptr);
     // execute without a GPU: argument checks first, then the stub reports the missing device
-    CHECK(tpx_plan(&m, &one, &one, &p) == TPX_OK);
+    CHECK(tpx_plan(&m, &one, &one, nullptr, &p) == TPX_OK);
     void* bufs[1] = {reinterpret_cast<void*>(0x1000)};
     CHECK(tpx_execute(p, bufs, bufs, nullptr, nullptr) == TPX_ERR_INVALID_ARG);
     CHECK(tpx_execute(p, bufs, bufs, reinterpret_cast<void*>(0x1000), nullptr) == TPX_ERR_HIP);
-    tpx_workspace_forget(p);
+    CHECK(tpx_execute(p, bufs, bufs, reinterpret_cast<void*>(0x1008), nullptr) == TPX_ERR_MISALIGNED);
+    void* odd[1] = {reinterpret_cast<void*>(0x1004)};
+    CHECK(tpx_execute(p, odd, bufs, reinterpret_cast<void*>(0x1000), nullptr) == TPX_ERR_MISALIGNED);
+    CHECK(tpx_execute_static(p, odd, bufs, nullptr) == TPX_ERR_MISALIGNED);
+    CHECK(tpx_execute_static(p, bufs, bufs, nullptr) == TPX_ERR_HIP);
+    tpx_workspace_forget(reinterpret_cast<void*>(0x1000));
+    tpx_workspace_forget(nullptr);
     tpx_free(p);
     tpx_free(nullptr);
   }

@@ -17,11 +17,7 @@ def _run(n, Bsz, D, D2, s, eb=8, how="boxes"):
     parts = ods.partition(G, Bsz, D)
     cur = ods.cursors_after(n, Bsz, D, s)
     want_parts, want_cur = ods.repartition(parts, cur, Bsz, D2)
-    tpx.tpx_set_option("tile_bytes", 4096)
-    try:
-        plan = tpx.tpx_plan_dataset(n, Bsz, D, D2, cur, index_elem_bytes=eb)
-    finally:
-        tpx.tpx_set_option("tile_bytes", 131072)
+    plan = tpx.tpx_plan_dataset(n, Bsz, D, D2, cur, index_elem_bytes=eb, opts=dict(tile_bytes=4096))
     assert plan.dst_cursors == want_cur
     assert [plan.buffer_bytes(0, j) for j in range(D)] == [p.nbytes for p in parts]
     assert [plan.buffer_bytes(1, j) for j in range(D2)] == [p.nbytes for p in want_parts]

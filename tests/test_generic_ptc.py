@@ -146,11 +146,7 @@ def test_generic_plan_matches_oracle(name, how):
     src, dst = CASES[name]
     a = H.np_bufs(src_buffers(src, 7))
     want = oreshard.reshard_ptc(src, dst, a)
-    tpx.tpx_set_option("tile_bytes", 4096)
-    try:
-        plan = plan_of(src, dst)
-    finally:
-        tpx.tpx_set_option("tile_bytes", 131072)
+    plan = plan_of(src, dst, opts=dict(tile_bytes=4096))
     got = [np.full(n, H.POISON, dtype=np.uint8) for _, n in dst]
     cover = [np.zeros(n, dtype=np.int32) for _, n in dst]
     (host_exec.run_boxes if how == "boxes" else host_exec.run_tiles)(plan, a, got, cover)
@@ -267,15 +263,73 @@ def test_generic_gpu_matches_oracle(cuda, name):
     src, dst = CASES[name]
     a = src_buffers(src, 9)
     want = oreshard.reshard_ptc(src, dst, H.np_bufs(a))
-    tpx.tpx_set_option("tile_bytes", 8192)
-    try:
-        plan = plan_of(src, dst)
-    finally:
-        tpx.tpx_set_option("tile_bytes", 131072)
+    plan = plan_of(src, dst, opts=dict(tile_bytes=8192))
     got, _ = G.execute(plan, [x.cuda() for x in a])
     torch.cuda.synchronize()
     for r in range(len(dst)):
         assert np.array_equal(got[r].cpu().numpy(), want[r]), r
+
+
+@pytest.mark.gpu
+def test_range_queries_and_json_collection_through_the_kernel(cuda):
+    """Section 5.2's range queries on a (3,2,1) job with transposed storage, and section 5.1's JSON-described collection,
+    executed by the HIP kernel; expected values from the oracle (full_tensor slices, reshard_ptc)."""
+    import json
+    from oracle import spec as ospec
+    from paper_2312_05181_amd import ptc_json
+    from tests import gpu_util as G
+    from tests.test_planner import SMALL, SMALL_MIX
+    model, par = SMALL, ospec.Parallel(3, 2, 1, w_transposed=1)
+    src = [ospec.rank_manifest(model, par, r) for r in range(par.n_ranks)]
+    cpu = H.make_src_bufs(model, par, 8, SMALL_MIX)
+    bufs = H.np_bufs(cpu)
+    lay = oreshard.Layout(manifests=src)
+    dense, qkv = ospec.tensor_id(ospec.DENSE_W, 1), ospec.tensor_id(ospec.QKV_W, 3)
+    queries = [(dense, 0, (0, 2), (24, 4)), (dense, 1, (5, 6), (9, 20)), (qkv, 1, (3, 1, 0, 7), (10, 3, 2, 19)),
+               (0, 0, (10, 0), (30, 24)), (ospec.tensor_id(ospec.FC1_B, 2), 0, (7,), (41,))]
+    plan = tpx.tpx_plan_query([[H.desc_of(e) for e in ent] for ent, _ in src], queries, src_bytes=[n for _, n in src])
+    got, _ = G.execute(plan, [x.cuda() for x in cpu])
+    torch.cuda.synchronize()
+    out = got[0].cpu().numpy()
+    covered = np.zeros(out.size, dtype=bool)
+    for q, e in zip(queries, plan.manifest(1, 0)):
+        full = oreshard.full_tensor(None, None, lay, q[0], q[1], lambda r, off, n: bufs[r][off:off + n])
+        want = np.ascontiguousarray(full[tuple(slice(l, h) for l, h in zip(q[2], q[3]))])
+        assert e.offset % 256 == 0 and e.nbytes == want.nbytes
+        assert np.array_equal(out[e.offset:e.offset + want.nbytes].view(want.dtype).reshape(want.shape), want), q
+        covered[e.offset:e.offset + want.nbytes] = True
+    assert (out[~covered] == H.POISON).all()
+
+    def gpu(t, T):
+        return {"mlp": {"fc1": {"weight": {"full_shape": [640, 96], "offset": [640 // T * t, 0], "shape": [640 // T, 96], "dtype": "bfloat16"},
+                                "bias": {"full_shape": [640], "offset": [640 // T * t], "shape": [640 // T], "dtype": "float32"}},
+                        "fc2": {"weight": {"full_shape": [96, 640], "offset": [0, 640 // T * t], "shape": [96, 640 // T], "dtype": "bfloat16",
+                                           "perm": [1, 0] if T == 4 else [0, 1]}}},
+                "ln": {"weight": {"full_shape": [96], "dtype": "float32"}}}
+    src_m, dst_m, _ = ptc_json.manifests_from_json(json.dumps([gpu(t, 2) for t in range(2)]), json.dumps([gpu(t, 4) for t in range(4)]))
+    plan = tpx.tpx_plan_ptc(src_m, dst_m, opts=dict(tile_bytes=4096))
+    src, dst = _collection_of(plan, 0), _collection_of(plan, 1)
+    a = []
+    for entries, n in src:
+        buf = torch.full((n,), H.SRC_GAP, dtype=torch.uint8)
+        for e in entries:
+            d = H.desc_of(e)
+            synth.fill_buffer(buf, [d], 1, ((d.elem_bytes, "index"),))
+        a.append(buf)
+    want = oreshard.reshard_ptc(src, dst, H.np_bufs(a))
+    got, _ = G.execute(plan, [x.cuda() for x in a])
+    torch.cuda.synchronize()
+    assert all(np.array_equal(g.cpu().numpy(), w) for g, w in zip(got, want))
+
+
+def _collection_of(plan, side):
+    """[(entries, buffer bytes)] per rank as the oracle takes them, read back from a plan's manifests."""
+    out = []
+    for r in range(plan.num_buffers(side)):
+        ent = [spec.Entry(e.tensor_id, e.kind, e.elem_bytes, e.offset, tuple(e.full_shape[:e.ndim]), tuple(e.lo[:e.ndim]),
+                          tuple(e.hi[:e.ndim]), tuple(e.perm[:e.ndim]), e.name, e.layer) for e in plan.manifest(side, r)]
+        out.append((ent, plan.buffer_bytes(side, r)))
+    return out
 
 
 def test_json_configuration_importer():
@@ -289,10 +343,12 @@ def test_json_configuration_importer():
                                 "bias": {"full_shape": [64], "offset": [64 // T * t], "shape": [64 // T], "dtype": "float32"}},
                         "fc2": {"weight": {"full_shape": [32, 64], "offset": [0, 64 // T * t], "shape": [32, 64 // T], "dtype": "bfloat16"}}},
                 "ln": {"weight": {"full_shape": [32], "dtype": "float32"}}}
-    src_m, dst_m, src_b, dst_b, names = ptc_json.manifests_from_json(json.dumps([gpu(0, 2), gpu(1, 2)]), json.dumps([gpu(0, 1)]))
+    src_m, dst_m, names = ptc_json.manifests_from_json(json.dumps([gpu(0, 2), gpu(1, 2)]), json.dumps([gpu(0, 1)]))
     assert names == ["/ln/weight", "/mlp/fc1/bias", "/mlp/fc1/weight", "/mlp/fc2/weight"]
-    to_entries = lambda mans, sizes: [([spec.Entry(*b[:10]) for b in m], n) for m, n in zip(mans, sizes)]
-    src, dst = to_entries(src_m, src_b), to_entries(dst_m, dst_b)
+    plan = tpx.tpx_plan_ptc(src_m, dst_m)           # the library places every block in its rank buffer
+    src, dst = _collection_of(plan, 0), _collection_of(plan, 1)
+    dst_b = [n for _, n in dst]
+    assert [e.offset for e in src[0][0]] == [0, 2048, 2304, 4352] and src[0][1] == 4608     # document order, 256-byte aligned
     mix = ((4, "index"),)
     a = []
     for entries, n in src:
@@ -302,7 +358,6 @@ def test_json_configuration_importer():
             synth.fill_buffer(buf, [d], 1, ((d.elem_bytes, "index"),))
         a.append(buf.numpy())
     want = oreshard.reshard_ptc(src, dst, a)
-    plan = tpx.tpx_plan_ptc(src_m, dst_m, src_bytes=src_b, dst_bytes=dst_b)
     got = [np.full(n, H.POISON, dtype=np.uint8) for n in dst_b]
     host_exec.run_tiles(plan, a, got)
     assert all(np.array_equal(g, w) for g, w in zip(got, want))

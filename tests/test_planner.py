@@ -31,8 +31,8 @@ def pk(par: Parallel, **extra) -> dict:
     return d
 
 
-def plan_for(model, src, dst, dst_alive=None, **kw):
-    return tpx.tpx_plan(mk(model), pk(src, **kw), pk(dst, rank_alive=dst_alive) if dst_alive is not None else pk(dst))
+def plan_for(model, src, dst, dst_alive=None, opts=None, **kw):
+    return tpx.tpx_plan(mk(model), pk(src, **kw), pk(dst, rank_alive=dst_alive) if dst_alive is not None else pk(dst), opts)
 
 
 def test_library_exports_every_declared_symbol():
@@ -117,13 +117,7 @@ def test_plan_interpreted_on_cpu_matches_oracle(model, mix, src, dst, how):
     destination tensor byte exactly once and touches nothing else."""
     src_bufs = H.np_bufs(H.make_src_bufs(model, src, 17, mix))
     want = oreshard.reshard(model, src, dst, src_bufs)
-    old = None
-    if how == "tiles":
-        tpx.tpx_set_option("tile_bytes", 4096)
-    try:
-        plan = plan_for(model, src, dst)
-    finally:
-        tpx.tpx_set_option("tile_bytes", 131072)
+    plan = plan_for(model, src, dst, opts=dict(tile_bytes=4096) if how == "tiles" else None)
     got = [np.full(plan.buffer_bytes(1, r), H.POISON, dtype=np.uint8) for r in range(dst.n_ranks)]
     cover = [np.zeros(len(g), dtype=np.int32) for g in got]
     (host_exec.run_boxes if how == "boxes" else host_exec.run_tiles)(plan, src_bufs, got, cover)
@@ -223,11 +217,7 @@ def test_share_reads_reads_every_piece_once(src, dst):
     src_bufs = H.np_bufs(H.make_src_bufs(model, src, 23, mix))
     want = oreshard.reshard(model, src, dst, src_bufs)
     local = plan_for(model, src, dst).stats()
-    tpx.tpx_set_option("share_reads", 1)
-    try:
-        plan = plan_for(model, src, dst)
-    finally:
-        tpx.tpx_set_option("share_reads", 0)
+    plan = plan_for(model, src, dst, opts=dict(share_reads=1))
     for how in (host_exec.run_boxes, host_exec.run_tiles):
         got = [np.full(plan.buffer_bytes(1, r), H.POISON, dtype=np.uint8) for r in range(dst.n_ranks)]
         how(plan, src_bufs, got)
@@ -417,9 +407,19 @@ def test_error_codes():
     odd_vocab = dict(m, vocab_true=37)
     assert st(lambda: tpx.tpx_plan(odd_vocab, dict(T=2, P=1, D=1), dict(T=1, P=1, D=1))) == B.TPX_ERR_INDIVISIBLE
     assert st(lambda: tpx.tpx_set_option("no_such_option", 1)) == B.TPX_ERR_INVALID_ARG
-    assert st(lambda: tpx.tpx_set_option("tile_bytes", 5000)) == B.TPX_ERR_INVALID_ARG
+    assert st(lambda: tpx.tpx_set_option("tile_bytes", 4096)) == B.TPX_ERR_INVALID_ARG      # a plan option, not a knob
+    assert st(lambda: tpx.tpx_set_option("streams", 0)) == B.TPX_ERR_INVALID_ARG
+    one = dict(T=1, P=1, D=1)
+    for bad_opts in (dict(tile_bytes=5000), dict(tile_bytes=2048), dict(max_multicast=129), dict(share_reads=2), dict(tiles=1)):
+        assert st(lambda: tpx.tpx_plan(m, one, one, bad_opts)) == B.TPX_ERR_INVALID_ARG
+    # lists whose length the library cannot check are checked by the binding
+    assert st(lambda: tpx.tpx_plan(m, dict(T=1, P=2, D=1, stage_first_layer=(0, 2)), one)) == B.TPX_ERR_INVALID_ARG
+    assert st(lambda: tpx.tpx_plan(m, dict(T=2, P=1, D=2, rank_alive=[1, 1, 1]), one)) == B.TPX_ERR_INVALID_ARG
+    assert st(lambda: tpx.tpx_plan(m, dict(T=1, P=2, D=1, layer_stage=(0, 1, 1)), one)) == B.TPX_ERR_INVALID_ARG
+    assert st(lambda: tpx.tpx_plan_ptc([[]], [[]], src_bytes=[0, 0])) == B.TPX_ERR_INVALID_ARG
+    assert st(lambda: tpx.tpx_plan_ptc([[]], [[]], src_alive=[1, 1])) == B.TPX_ERR_INVALID_ARG
     import ctypes as C
-    assert B._lib.tpx_plan(None, None, None, None) == B.TPX_ERR_INVALID_ARG
+    assert B._lib.tpx_plan(None, None, None, None, None) == B.TPX_ERR_INVALID_ARG
     assert B._lib.tpx_execute(None, None, None, None, None) == B.TPX_ERR_INVALID_ARG
     assert b"NULL" in B._lib.tpx_last_error()
     assert B._lib.tpx_num_buffers(None, 0) == 0 and B._lib.tpx_workspace_bytes(None) == 0

@@ -58,11 +58,7 @@ def test_random_gpt_configurations(seed):
     mix = tuple((eb, "index") for eb in model.state_elem_bytes)
     src_bufs = H.np_bufs(H.make_src_bufs(model, src, seed, mix))
     want = oreshard.reshard(model, src, dst, src_bufs)
-    tpx.tpx_set_option("tile_bytes", 4096)
-    try:
-        plan = plan_for(model, src, dst)
-    finally:
-        tpx.tpx_set_option("tile_bytes", 131072)
+    plan = plan_for(model, src, dst, opts=dict(tile_bytes=4096))
     for how in (host_exec.run_boxes, host_exec.run_tiles):
         got = [np.full(plan.buffer_bytes(1, r), H.POISON, dtype=np.uint8) for r in range(dst.n_ranks)]
         cover = [np.zeros(len(g), dtype=np.int32) for g in got]
@@ -136,11 +132,7 @@ def random_explicit_case(seed, dims):
 @pytest.mark.parametrize("seed", range(40))
 def test_random_explicit_collections(seed):
     src, dst, a, want = random_explicit_case(seed, [1, 2, 3, 5, 8, 16, 24])
-    tpx.tpx_set_option("tile_bytes", 4096)
-    try:
-        plan = plan_of(src, dst)
-    finally:
-        tpx.tpx_set_option("tile_bytes", 131072)
+    plan = plan_of(src, dst, opts=dict(tile_bytes=4096))
     for how in (host_exec.run_boxes, host_exec.run_tiles):
         got = [np.full(n, H.POISON, dtype=np.uint8) for _, n in dst]
         how(plan, a, got)
@@ -157,11 +149,7 @@ def test_random_explicit_collections_gpu(cuda, seed, dims):
     from tests import gpu_util as G
     src, dst, a, want = random_explicit_case(seed, dims)
     print("seed", seed, "dims", dims[-1], "bytes", sum(n for _, n in dst), flush=True)
-    tpx.tpx_set_option("tile_bytes", 4096 if dims[-1] < 100 else 131072)
-    try:
-        plan = plan_of(src, dst)
-    finally:
-        tpx.tpx_set_option("tile_bytes", 131072)
+    plan = plan_of(src, dst, opts=dict(tile_bytes=4096 if dims[-1] < 100 else 131072))
     got, _ = G.execute(plan, [torch.from_numpy(x).cuda() for x in a])
     torch.cuda.synchronize()
     for r in range(len(dst)):
@@ -178,11 +166,7 @@ def test_random_gpt_configurations_gpu(cuda, seed):
     mix = tuple((eb, "index") for eb in model.state_elem_bytes)
     src_cpu = H.make_src_bufs(model, src, seed, mix)
     want = oreshard.reshard(model, src, dst, H.np_bufs(src_cpu))
-    tpx.tpx_set_option("tile_bytes", 4096)
-    try:
-        plan = plan_for(model, src, dst)
-    finally:
-        tpx.tpx_set_option("tile_bytes", 131072)
+    plan = plan_for(model, src, dst, opts=dict(tile_bytes=4096))
     got, _ = G.execute(plan, [b.cuda() for b in src_cpu])
     torch.cuda.synchronize()
     for r in range(dst.n_ranks):

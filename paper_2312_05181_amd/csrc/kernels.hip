@@ -143,6 +143,7 @@ struct SegLds {
   uint64_t pitch;
 };
 constexpr uint32_t kMaxSegLds = 64;
+constexpr int kSegLdsBytes = int(kMaxSegLds * sizeof(SegLds));
 
 template <int kThreads, int U, bool NTL, bool NTS>
 __device__ __forceinline__ void merge_tile(const tpx_tile& t, const tpx_segment* __restrict__ segs, const uint8_t* const* src_table,
@@ -235,6 +236,104 @@ __device__ __forceinline__ void transpose_tile(const uint8_t* __restrict__ s, ui
     }
 }
 
+// ---- one-shot transposing block ---------------------------------------------------------------------------
+// A block of TI x TJ elements (tpx::kBlockBytes in all): element (i, j) sits at s + i*sp + j*sizeof(E) and goes to
+// d + j*dstep + i*sizeof(E).  Like a copy tile it is moved in one shot: every thread issues all its 16-byte loads
+// (the whole block is in flight), the block passes through LDS once, and every thread issues all its 16-byte
+// stores.  The unit of the exchange is a micro-block of VE x VE elements (VE = 16 / sizeof(E)): a thread loads its
+// VE row vectors (consecutive lanes take consecutive vectors of a row: coalesced), transposes them in registers
+// (pure renaming for 4- and 8-byte elements, 16-bit packs for 2-byte ones) and writes VE column vectors to LDS,
+// which is laid out like the destination block: TJ rows of TI elements, i.e. IB = TI / VE chunks of 16 bytes.
+// Chunk c of row r is kept at position c ^ ((r / VE) & 7): the lanes of a write (same c, rows VE apart) and of a
+// read (same r, consecutive c) then fall on different banks, with no padding.
+template <typename E>
+struct MicroBlock {
+  static constexpr int VE = 16 / int(sizeof(E));
+  // out[k] = (in[0] element k, in[1] element k, ..., in[VE-1] element k)
+  static __device__ __forceinline__ void transpose(const v4u (&in)[VE], v4u (&out)[VE]) {
+    if constexpr (sizeof(E) == 4) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) out[k] = v4u{in[0][k], in[1][k], in[2][k], in[3][k]};
+    } else if constexpr (sizeof(E) == 8) {
+      out[0] = v4u{in[0][0], in[0][1], in[1][0], in[1][1]};
+      out[1] = v4u{in[0][2], in[0][3], in[1][2], in[1][3]};
+    } else {
+      static_assert(sizeof(E) == 2, "element size");
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        // halves k of dword k/2: low halves (bytes 0,1 of each source) for even k, high halves (bytes 2,3) for odd k
+        const unsigned sel = (k & 1) ? 0x07060302u : 0x05040100u;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) out[k][w] = __builtin_amdgcn_perm(in[2 * w + 1][k >> 1], in[2 * w][k >> 1], sel);
+      }
+    }
+  }
+};
+
+template <typename E, int TI, int TJ, int kThreads, bool NTL, bool NTS>
+__device__ __forceinline__ void transpose_block(const uint8_t* __restrict__ s, const DstSet& ds, uint64_t sp, uint64_t dstep,
+                                                void* lds_raw) {
+  constexpr int VE = MicroBlock<E>::VE;
+  constexpr int IB = TI / VE, JB = TJ / VE;   // micro-blocks along i and j; IB is also the 16-byte chunks of an LDS row
+  constexpr int PER = IB * JB / kThreads;     // micro-blocks per thread
+  static_assert(TI * TJ * int(sizeof(E)) == int(tpx::kBlockBytes) && IB % 8 == 0 && (IB * JB) % kThreads == 0 && PER >= 1, "block shape");
+  v4u* lds = reinterpret_cast<v4u*>(lds_raw);
+  v4u r[PER][VE];
+#pragma unroll
+  for (int m = 0; m < PER; ++m) {
+    const uint32_t mb = threadIdx.x + m * kThreads, jb = mb % JB, ib = mb / JB;
+#pragma unroll
+    for (int q = 0; q < VE; ++q)
+      r[m][q] = ld<v4u, NTL>(reinterpret_cast<const v4u*>(s + uint64_t(ib * VE + q) * sp + jb * 16));
+  }
+#pragma unroll
+  for (int m = 0; m < PER; ++m) {
+    const uint32_t mb = threadIdx.x + m * kThreads, jb = mb % JB, ib = mb / JB;
+    v4u c[VE];
+    MicroBlock<E>::transpose(r[m], c);
+#pragma unroll
+    for (int k = 0; k < VE; ++k) lds[(jb * VE + k) * IB + (ib ^ (jb & 7))] = c[k];
+  }
+  __syncthreads();
+  constexpr int NV = PER * VE;  // 16-byte vectors per thread
+  v4u w[NV];
+#pragma unroll
+  for (int n = 0; n < NV; ++n) {
+    const uint32_t q = threadIdx.x + n * kThreads, c = q % IB, row = q / IB;
+    w[n] = lds[row * IB + (c ^ ((row / VE) & 7))];
+  }
+  for (uint32_t k = 0; k < ds.n; ++k) {
+    uint8_t* d = ds.base(k);
+#pragma unroll
+    for (int n = 0; n < NV; ++n) {
+      const uint32_t q = threadIdx.x + n * kThreads, c = q % IB, row = q / IB;
+      st<v4u, NTS>(reinterpret_cast<v4u*>(d + row * dstep + c * 16), w[n]);
+    }
+  }
+}
+
+// True if the tile was a full, 16-byte aligned block of a shape moved in one shot (and has been moved).
+template <typename E, int kThreads, bool NTL, bool NTS>
+__device__ __forceinline__ bool transpose_one_shot(const uint8_t* s, const DstSet& ds, const tpx_tile& t, void* lds_raw) {
+  if constexpr (kThreads != 512 || sizeof(E) == 1) {
+    return false;
+  } else {
+    if (uint64_t(t.nrows) * t.run_units * sizeof(E) != tpx::kBlockBytes) return false;
+    uint64_t bits = reinterpret_cast<uintptr_t>(s) | t.src_pitch | t.dst_step;
+    for (uint32_t k = 0; k < ds.n; ++k) bits |= reinterpret_cast<uintptr_t>(ds.base(k));
+    if (bits % 16) return false;
+    constexpr int kElems = int(tpx::kBlockBytes) / int(sizeof(E));
+    switch (t.nrows) {  // the shapes tpx::block_i can ask for
+      case 64: transpose_block<E, 64, kElems / 64, kThreads, NTL, NTS>(s, ds, t.src_pitch, t.dst_step, lds_raw); break;
+      case 128: transpose_block<E, 128, kElems / 128, kThreads, NTL, NTS>(s, ds, t.src_pitch, t.dst_step, lds_raw); break;
+      case 256: transpose_block<E, 256, kElems / 256, kThreads, NTL, NTS>(s, ds, t.src_pitch, t.dst_step, lds_raw); break;
+      case 512: transpose_block<E, 512, kElems / 512, kThreads, NTL, NTS>(s, ds, t.src_pitch, t.dst_step, lds_raw); break;
+      default: return false;
+    }
+    return true;
+  }
+}
+
 template <typename E, int kThreads>
 __device__ __forceinline__ void gather_tile(const uint8_t* __restrict__ s, uint8_t* __restrict__ d, const tpx_tile& t) {
   const uint32_t total = t.run_units * t.nrows;
@@ -245,9 +344,9 @@ __device__ __forceinline__ void gather_tile(const uint8_t* __restrict__ s, uint8
   }
 }
 
-constexpr int kLdsBytes = TransposeShape<uint16_t>::kBytes;  // the largest transposing sub-tile (33,024 bytes)
-static_assert(kLdsBytes >= TransposeShape<uint8_t>::kBytes && kLdsBytes >= TransposeShape<uint32_t>::kBytes &&
-                  kLdsBytes >= TransposeShape<uint64_t>::kBytes, "LDS budget");
+constexpr int kLdsBytes = int(tpx::kBlockBytes);  // a one-shot block; the general path's sub-tiles are smaller
+static_assert(kLdsBytes >= TransposeShape<uint8_t>::kBytes && kLdsBytes >= TransposeShape<uint16_t>::kBytes &&
+                  kLdsBytes >= TransposeShape<uint32_t>::kBytes && kLdsBytes >= TransposeShape<uint64_t>::kBytes, "LDS budget");
 
 template <int kThreads, int U, bool NTL, bool NTS>
 __global__ __launch_bounds__(kThreads) void tpx_execute_tiles(const tpx::WorkspaceHeader* __restrict__ header, uint64_t plan_id,
@@ -256,8 +355,10 @@ __global__ __launch_bounds__(kThreads) void tpx_execute_tiles(const tpx::Workspa
                                                               const uint32_t* __restrict__ coarse,
                                                               const tpx_segment* __restrict__ segs, uint32_t n_boxes,
                                                               uint32_t n_tiles, uint32_t streams, PtrTable ptrs) {
+  // dynamic LDS only: the segment table of a merge tile or the staging block of a transposing tile (a workgroup
+  // executes one tile, so the two never coexist)
   extern __shared__ __align__(16) uint8_t lds_raw[];
-  __shared__ SegLds lseg[kMaxSegLds];
+  SegLds* lseg = reinterpret_cast<SegLds*>(lds_raw);
   // The tables behind `header` must be the ones this launch was made for (a workspace recycled for another
   // plan since the upload would send the moves anywhere): otherwise the whole grid does nothing.
   if (header->plan_id != plan_id) return;
@@ -291,7 +392,17 @@ __global__ __launch_bounds__(kThreads) void tpx_execute_tiles(const tpx::Workspa
     else move_rows_any<kThreads, U, NTL, NTS, false, false>(t.unit_log2, s, ds, t.run_units, t.nrows, t.src_pitch, t.dst_pitch);
     return;
   }
-  // transposing and gathering tiles: one pass per destination (they are rare; the source is re-read)
+  if (t.kind == TPX_TILE_TRANSPOSE) {  // full blocks in one shot; ragged or misaligned ones fall through to the general path
+    bool done = false;
+    switch (t.unit_log2) {
+      case 3: done = transpose_one_shot<uint64_t, kThreads, NTL, NTS>(s, ds, t, lds_raw); break;
+      case 2: done = transpose_one_shot<uint32_t, kThreads, NTL, NTS>(s, ds, t, lds_raw); break;
+      case 1: done = transpose_one_shot<uint16_t, kThreads, NTL, NTS>(s, ds, t, lds_raw); break;
+      default: break;
+    }
+    if (done) return;
+  }
+  // other transposing tiles and gathering tiles: one pass per destination (they are rare; the source is re-read)
   for (uint32_t c = 0; c < t.n_dst; ++c) {
     uint8_t* d = ds.base(c);
     if (t.kind == TPX_TILE_TRANSPOSE) {
@@ -396,17 +507,16 @@ tpx_status hip_launch_tiles(const void* workspace, const tpx_plan_s& plan, const
   const uint8_t* base = static_cast<const uint8_t*>(workspace);
   const bool automatic = variant == 0;
   if (automatic) {
-    // a workgroup should load its whole tile at once (threads x loads in flight x 16 bytes = tile); transposing
-    // tiles serialise load / LDS / store phases inside a workgroup, so they want several small workgroups
-    // per CU to overlap each other
-    variant = plan.needs_lds                 ? (2 | 24)              //  256 threads x 4
+    // a workgroup should load its whole tile at once (threads x loads in flight x 16 bytes = tile); a plan with
+    // transposing tiles has 64 KiB tiles and blocks, two workgroups of 512 threads per CU (LDS: 2 x 65 KiB)
+    variant = plan.needs_lds                 ? (3 | 24 | (1 << 5))   //  512 threads x 8
             : plan.tile_bytes_used >= 131072 ? (3 | 24 | (2 << 5))   // 1024 threads x 8
             : plan.tile_bytes_used >= 65536  ? (3 | 24 | (1 << 5))   //  512 threads x 8
                                              : (2 | 24);             //  256 threads x 4 (small jobs, small tiles)
   }
   // interleaving several parts of the plan pays only when tiles cost the same; a plan that mixes plain and
-  // replicated moves, or has transposing tiles, runs in plan order
-  const uint32_t streams = plan.uniform_tiles && !(automatic && plan.needs_lds) ? uint32_t(std::max<uint64_t>(1, tuning().streams.load())) : 1;
+  // replicated moves runs in plan order
+  const uint32_t streams = plan.uniform_tiles ? uint32_t(std::max<uint64_t>(1, tuning().streams.load())) : 1;
   const uint32_t grid = uint32_t((plan.n_tiles + streams - 1) / streams * streams);
   KernelFn k = pick_kernel(variant);
   const WorkspaceHeader* a_header = reinterpret_cast<const WorkspaceHeader*>(base + w.header_off);
@@ -419,7 +529,7 @@ tpx_status hip_launch_tiles(const void* workspace, const tpx_plan_s& plan, const
   void* args[] = {&a_header, &a_id, &a_boxes, &a_first, &a_coarse, &a_segs, &a_nboxes, &a_ntiles, &a_streams, &pt};
   // the launch's own status, not the runtime's last-error slot, which other users of the runtime share
   const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(k), dim3(grid), dim3(threads_of(variant)), args,
-                                       plan.needs_lds ? kLdsBytes : 0, static_cast<hipStream_t>(stream));
+                                       plan.needs_lds ? kLdsBytes : kSegLdsBytes, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return hip_fail(e, "launching the tile kernel");
   return TPX_OK;
 }

@@ -298,6 +298,8 @@ tpx_status tile_boxes(tpx_plan_s& plan, uint64_t tile_bytes) {
   plan.flat.clear();
   uint64_t total = 0;
   for (const tpx_box& b : plan.boxes) total += box_bytes(b);
+  for (const tpx_box& b : plan.boxes)  // a plan with transposing moves runs workgroups sized for their blocks
+    if (b.kind == TPX_BOX_TRANSPOSE) tile_bytes = std::min<uint64_t>(tile_bytes, kBlockBytes);
   while (tile_bytes > 16384 && total / tile_bytes < 8192) tile_bytes >>= 1;
   plan.tile_bytes_used = tile_bytes;
   plan.segments.clear();
@@ -383,8 +385,17 @@ tpx_status tile_boxes(tpx_plan_s& plan, uint64_t tile_bytes) {
       f.dst_step = b.dst_stride[J];
       f.src_pitch = (I == J) ? 0 : b.src_stride[I];
       f.dst_pitch = (I == J) ? 0 : b.dst_stride[I];
-      f.rows_per_tile = uint32_t(std::min<uint64_t>(nI, 256));
-      f.chunk_units = uint32_t(std::max<uint64_t>(64, std::min<uint64_t>(nJ, tile_bytes / (f.rows_per_tile * eb))));
+      const uint32_t bi = plane ? block_i(uint32_t(eb), nI) : 0;
+      if (bi) {  // blocks the kernel moves in one shot
+        // consecutive workgroups then write neighbouring segments of the same destination rows: the scattered side
+        // is the reads, which take it better (measured: 5.85 -> 6.0 TB/s on the 1.3B-shape transposing reshard)
+        f.rows_first = 1;
+        f.rows_per_tile = bi;
+        f.chunk_units = uint32_t(kBlockBytes / (bi * eb));
+      } else {
+        f.rows_per_tile = uint32_t(std::min<uint64_t>(nI, 256));
+        f.chunk_units = uint32_t(std::max<uint64_t>(64, std::min<uint64_t>(nJ, tile_bytes / (f.rows_per_tile * eb))));
+      }
     } else {
       // COPY / FILL: the unit is the widest power of two (<= 16 bytes) that divides every offset, pitch
       // and the run length; buffer bases are required to be 16-byte aligned.

@@ -37,11 +37,25 @@ struct FlatBox {
   uint32_t seg_first;       // MERGE boxes: first entry in the segment table, segments per row,
   uint32_t n_seg;           // units per segment
   uint32_t seg_units;
-  uint32_t pad_;
+  uint32_t rows_first;      // tile order inside the box: 0 = along a row of tiles first, 1 = down a column of tiles first
 };
 static_assert(sizeof(FlatBox) == 96, "FlatBox layout");
 
 constexpr uint32_t kCoarseShift = 6;  // one coarse entry per 64 tiles
+
+// Transposing tiles that the kernel moves in one shot (whole tile in flight, staged once through LDS) are
+// kBlockBytes large.  For an element of eb bytes the planner cuts a transposing move into blocks of
+// block_i(eb, nI) elements along the axis that is contiguous on the destination (nI its extent) by
+// kBlockBytes / (block_i * eb) elements along the axis that is contiguous on the source: 1 KiB destination
+// segments where the move is that long, never fewer than 64 elements.  0 = no one-shot shape for this element
+// size (the general path is used).
+constexpr uint32_t kBlockBytes = 65536;
+TPX_HD uint32_t block_i(uint32_t eb, uint64_t nI) {
+  if (eb != 2 && eb != 4 && eb != 8) return 0;
+  uint32_t want = 1024 / eb;
+  while (want > nI && want > 64) want >>= 1;
+  return want;
+}
 
 TPX_HD uint32_t tiles_of(const FlatBox& b) {
   return ((b.nrows + b.rows_per_tile - 1) / b.rows_per_tile) * b.chunks_per_row;
@@ -63,8 +77,15 @@ TPX_HD uint32_t find_box(const uint32_t* first_tile, const uint32_t* coarse, uin
 // The `local`-th tile of box b.
 TPX_HD tpx_tile tile_of(const FlatBox& b, uint32_t local) {
   tpx_tile t{};
-  const uint32_t rb = local / b.chunks_per_row;
-  const uint32_t c = local - rb * b.chunks_per_row;
+  uint32_t rb, c;
+  if (b.rows_first) {  // consecutive tiles advance along the rows (the destination-contiguous axis of a transposing box)
+    const uint32_t nrb = (b.nrows + b.rows_per_tile - 1) / b.rows_per_tile;
+    c = local / nrb;
+    rb = local - c * nrb;
+  } else {
+    rb = local / b.chunks_per_row;
+    c = local - rb * b.chunks_per_row;
+  }
   const uint32_t row0 = rb * b.rows_per_tile;
   const uint32_t col0 = c * b.chunk_units;
   t.nrows = b.nrows - row0 < b.rows_per_tile ? b.nrows - row0 : b.rows_per_tile;

@@ -8,8 +8,9 @@ region.  Steps run back to back, so the host planning of one step overlaps the k
 one; the latency of a single isolated reconfiguration is reported separately.
 
 Prints one JSON line.  `value` is state bytes read + written per second of step time; `roofline`
-describes the copy kernel alone, timed with HIP events on the launch stream; `cpu_baseline` is the
-CPU oracle timed on a bounded sample of the same workload.
+describes the copy kernel alone, timed with HIP events on the launch stream (`traffic` comes from the
+counter record under profiles/ and is null unless that record was taken on the present library sources and
+plan); `cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
@@ -89,19 +90,39 @@ DATASET_WORKLOAD = "dataset_1e8_D6->D4"
 DATASET_CFG = dict(n_samples=10 ** 8, global_batch=768, D_src=6, D_dst=4, steps_done=65000, seed=6)
 DEFAULT_WORKLOAD = "gpt6.7b_(8,1,1)->(1,8,1)"
 
-# HBM bytes per launch of the copy kernel, measured with rocprofv3 FETCH_SIZE / WRITE_SIZE passes scaled by a plain
-# copy of known size (the summaries under profiles/ give the raw counter values), or None where not measured.
-MEASURED_TRAFFIC = {
-    "gpt6.7b_(8,1,1)->(1,8,1)": 186359356682,
-    "gpt1.3b_(4,2,1)->(2,4,1)": 36857000000,
-    "gpt2.7b_(4,4,2)->(2,4,1)": 74272000000,
-    "gpt_h3072_T3->T4_padded_vocab": 80869000000,
-    "gpt1.3b_(4,2,1)->(4,2,2)_dp": 55526000000,
-    "bert-large_(1,1,4)->(1,1,8)": 60847000000,
-    "gpt2.7b_(2,2,4)->(4,2,2)_sharded_opt": 85078000000,
-    "bert-large_(1,1,4)->(1,1,8)|share_reads": 42149670154,
-    "gpt1.3b_(4,2,1)->(2,4,1)_transposed_dst": 36855000000,
-}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+
+
+def source_hash() -> str:
+    """Fingerprint of everything that decides what the kernel does and what a plan contains: the library's sources."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    files = sorted(glob.glob(os.path.join(ROOT, "paper_2312_05181_amd", "csrc", "*"))) + [os.path.join(ROOT, "include", "tpx.h")]
+    for path in files:
+        h.update(os.path.basename(path).encode())
+        with open(path, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(key: str, stats: dict):
+    """HBM bytes per launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes recorded in profiles/hbm_traffic.json
+    (counter means in KiB, each scaled by what the same counter read for a plain copy of known size in the same run),
+    or None with the reason when the record was not taken on these sources and this plan."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            rec = json.load(f)["workloads"].get(key)
+    except (OSError, ValueError, KeyError):
+        rec = None
+    if rec is None:
+        return None, "no counter record for this workload"
+    if rec["source_hash"] != source_hash():
+        return None, "the counter record was taken on other library sources"
+    if rec["n_tiles"] != stats["n_tiles"] or rec["algorithmic_bytes"] != stats["bytes_read"] + stats["bytes_written"]:
+        return None, "the counter record was taken on a different plan"
+    traffic = int(round(1024 * (rec["fetch_size_kib"] * rec["fetch_scale"] + rec["write_size_kib"] * rec["write_scale"])))
+    return traffic, rec["profile"]
 
 
 def main() -> int:
@@ -213,15 +234,17 @@ def main() -> int:
     latency_ms = sorted(lat)[len(lat) // 2]
 
     achieved = state_bytes / (kernel_ms_avg * 1e-3) / 1e9
+    traffic, traffic_from = measured_traffic(args.workload + ("|share_reads" if args.share_reads else ""), stats)
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": MEASURED_TRAFFIC.get(args.workload + ("|share_reads" if args.share_reads else "")),
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic, "traffic_from": traffic_from,
                 "kernel": "tpx_execute_tiles", "kernel_ms_avg": round(kernel_ms_avg, 4),
                 "kernel_ms_min": round(min(kernel_ms), 4), "algorithmic_bytes_per_launch": state_bytes}
 
-    probe = memcpy_probe = None
+    probe = memcpy_probe = probe_bytes = None
     if not args.no_probe:
         n = min(8 << 30, min(b.numel() for b in src_bufs if b.numel()) // 16 * 16, dst_bufs[0].numel() // 16 * 16)
         a, b = src_bufs[0], dst_bufs[0]
+        probe_bytes = n
         for _ in range(2):
             tpx.tpx_probe_copy(b.data_ptr(), a.data_ptr(), n, stream)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -262,6 +285,7 @@ def main() -> int:
                             "isolated_plan_upload_kernel": round(latency_ms, 4),
                             "back_to_back_step": round(ms_per_step, 4)},
         "copy_probe_GBps": probe,
+        "copy_probe_bytes": probe_bytes,
         "memcpy_d2d_GBps": memcpy_probe,
         "setup_s": round(setup_s, 1),
         "roofline": roofline,
@@ -321,6 +345,7 @@ def bench_dataset(args) -> int:
     kernel_ms = [a.elapsed_time(b_) for a, b_ in evs]
     kavg = sum(kernel_ms) / len(kernel_ms)
     achieved = state_bytes / (kavg * 1e-3) / 1e9
+    traffic, traffic_from = measured_traffic(args.workload, stats)
     del keep
 
     cpu = None
@@ -342,7 +367,8 @@ def bench_dataset(args) -> int:
                       "src_ranks": D, "dst_ranks": D2},
            "pct_of_hbm_peak": round(100 * achieved / HBM_PEAK_GBPS, 2),
            "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                        "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None, "kernel": "tpx_execute_tiles",
+                        "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic, "traffic_from": traffic_from,
+                        "kernel": "tpx_execute_tiles",
                         "kernel_ms_avg": round(kavg, 4), "kernel_ms_min": round(min(kernel_ms), 4),
                         "algorithmic_bytes_per_launch": state_bytes},
            "cpu_baseline": cpu}

@@ -442,8 +442,9 @@ def cpu_baseline(args, model, src, dst, plan, src_bufs, dst_bufs, src_ptrs, dst_
             ok = ok and bool(np.array_equal(have, block.reshape(-1).view(np.uint8)))
     return {"value": round(moved / secs / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
             "sample": f"all state tensors of the first {layers} of {om.n_layers} layers "
-                      f"({moved / 2e9:.2f} GB read + the same written), numpy, {threads} threads over tensors, "
-                      f"mean of {passes} passes",
+                      f"({moved / 2e9:.2f} GB read + the same written, counted on the oracle's output: where the new "
+                      f"configuration does not slice a tensor its re-slice is a view and only the paste copies), numpy, "
+                      f"{threads} threads over tensors, mean of {passes} passes",
             "seconds": round(secs, 2), "host_cpus_online": os.cpu_count(), "host_cpu_model": _cpu_model(),
             "gpu_matches_oracle_on_sample": ok}
 

@@ -136,10 +136,12 @@ typedef struct {
                                  columns on the destination (dst_pitch == unit); staged through LDS */
 #define TPX_TILE_GATHER 3u    /* unit = element; arbitrary steps (degenerate transposes) */
 #define TPX_TILE_MERGE 4u     /* the merge of algorithm 1 done inside the tile: destination rows are written whole;
-                                 columns [k*seg_units, (k+1)*seg_units) of every row come from segment
-                                 seg_first + k (its own source buffer, offset and row pitch), k < n_seg;
-                                 src_off / src_pitch / src_rank are unused, src_off = first row of the tile
-                                 within the box (add src_off * segment pitch to the segment's offset) */
+                                 every row is the concatenation of n_seg column blocks, block k coming from
+                                 segment seg_first + k (its own source buffer, offset, row pitch and width);
+                                 seg_units = the common width of the blocks in units, or 0 when they differ
+                                 (then see tpx_segment.units); src_off / src_pitch / src_rank are unused,
+                                 src_off = first row of the tile within the box (add src_off * segment pitch
+                                 to the segment's offset) */
 typedef struct {
   uint64_t src_off, dst_off;  /* bytes, inside the rank buffers */
   uint64_t src_pitch, dst_pitch;
@@ -162,7 +164,7 @@ typedef struct {
   uint64_t src_off;           /* byte offset of row 0 of the box in buffer src_rank */
   uint64_t src_pitch;         /* bytes between rows */
   uint32_t src_rank;
-  uint32_t pad_;
+  uint32_t units;             /* width of the column block it contributes, in 16-byte units */
 } tpx_segment;
 
 typedef struct {
@@ -178,8 +180,8 @@ typedef struct {
 
 /* Options of one plan; NULL wherever a tpx_plan_opts* is taken means all defaults (a zero field too).
  *   tile_bytes     upper bound of bytes per tile, the unit of GPU work: a power of two, 4096 .. 4194304; default
- *                  131072.  Small jobs use smaller tiles, down to 16384, so that the launch still has thousands of
- *                  workgroups.
+ *                  65536.  Small jobs use smaller tiles, down to 16384, so that the launch still has thousands of
+ *                  workgroups; a plan with transposing moves never uses larger ones.
  *   max_multicast  most replicas one move may be written to (1 .. 128; default 8; 1 = every replica is copied
  *                  separately).
  *   share_reads    0 (default): every destination rank reads from the holder section 6.5's locality rule picks for
@@ -353,12 +355,17 @@ const char* tpx_last_error(void);
 
 /* Process-wide knobs of the executor, for experiments with the kernel (each is read and written atomically by
  * any thread; what a plan contains never depends on them):
- *   "variant"     kernel variant, 0 (default) = chosen from the tile size: 1024 threads per workgroup with eight
- *                 nontemporal 16-byte loads in flight per thread for 128 KiB tiles, smaller workgroups for
- *                 smaller tiles; other values are a bit field documented in the kernel source
- *   "streams"     tile order (1 .. 1024; default 4): workgroup b executes the (b / streams)-th tile of the
- *                 (b % streams)-th contiguous part of the plan, so concurrent workgroups touch `streams`
- *                 distant regions of the buffers
+ *   "variant"     kernel variant, 0 (default) = chosen from the tile size: 512 threads per workgroup with eight
+ *                 nontemporal 16-byte loads in flight per thread for 64 KiB tiles, 1024 threads for tiles of 128 KiB
+ *                 and more, 256 threads x 4 loads for smaller tiles; other values are a bit field documented in the
+ *                 kernel source
+ *   "streams"     tile order (1 .. 1024; default 4): the tile sequence is cut into `streams` contiguous parts that
+ *                 advance side by side, so concurrent workgroups touch `streams` distant regions of the buffers
+ *   "chunk"       tile order (0 .. 4096; default 0 = automatic: 8, or 1 for plans with transposing moves): within a
+ *                 stream, each of the GPU's 8 XCDs takes `chunk` consecutive tiles at a time (used when `streams`
+ *                 divides 8); 1 = workgroup b takes the (b / streams)-th tile of stream b % streams
+ *   "occupancy"   workgroups per CU, enforced through the LDS size a workgroup requests (0 .. 16; default 0 =
+ *                 automatic: one for 512-thread workgroups, unconstrained otherwise)
  * Errors: INVALID_ARG for an unknown key or a value out of range. */
 tpx_status tpx_set_option(const char* key, uint64_t value);
 

@@ -77,7 +77,7 @@ class tpx_tile(C.Structure):
 
 
 class tpx_segment(C.Structure):
-    _fields_ = [("src_off", C.c_uint64), ("src_pitch", C.c_uint64), ("src_rank", C.c_uint32), ("pad_", C.c_uint32)]
+    _fields_ = [("src_off", C.c_uint64), ("src_pitch", C.c_uint64), ("src_rank", C.c_uint32), ("units", C.c_uint32)]
 
 
 class tpx_ptc(C.Structure):

@@ -350,6 +350,16 @@ tpx_status tpx_set_option(const char* key, uint64_t value) {
     tuning().variant = value;
     return TPX_OK;
   }
+  if (!std::strcmp(key, "chunk")) {
+    if (value > 4096) return fail(TPX_ERR_INVALID_ARG, "chunk must be in [0, 4096]");
+    tuning().chunk = value;
+    return TPX_OK;
+  }
+  if (!std::strcmp(key, "occupancy")) {
+    if (value > 16) return fail(TPX_ERR_INVALID_ARG, "occupancy must be in [0, 16]");
+    tuning().occupancy = value;
+    return TPX_OK;
+  }
   if (!std::strcmp(key, "streams")) {
     if (value < 1 || value > 1024) return fail(TPX_ERR_INVALID_ARG, "streams must be in [1, 1024]");
     tuning().streams = value;

@@ -59,9 +59,11 @@ tpx_status plan_dataset_moves(tpx_plan_s& plan, uint64_t n, uint32_t B, uint32_t
   // split + move + merge on the column axis
   plan.boxes.clear();
   uint64_t pieces = 0;
+  std::vector<tpx_box> tails;
   for (uint32_t jn = 0; jn < Dn; ++jn) {
     uint64_t pos = jn * bn;
     const uint64_t end = (jn + 1) * bn;
+    tails.clear();  // the pieces of the whole steps stay neighbours in the list (they merge into whole new rows); the ragged step follows
     while (pos < end) {
       const uint64_t j = pos / b;
       const uint64_t cut = std::min(end, (j + 1) * b);
@@ -96,10 +98,11 @@ tpx_status plan_dataset_moves(tpx_plan_s& plan, uint64_t n, uint32_t B, uint32_t
         bx.src_off = (full * b + (pos - j * b)) * eb;
         bx.dst_off = (full * bn + (pos - jn * bn)) * eb;
         bx.run_bytes = (std::min(cut, tail) - pos) * eb;
-        plan.boxes.push_back(bx);
+        tails.push_back(bx);
       }
       pos = cut;
     }
+    plan.boxes.insert(plan.boxes.end(), tails.begin(), tails.end());
   }
   plan.stats.n_pieces = pieces;
   return TPX_OK;

@@ -135,34 +135,49 @@ __device__ __forceinline__ void move_rows_any(uint32_t unit_log2, const uint8_t*
   }
 }
 
-// Merge tile: whole destination rows of row_units 16-byte units are written contiguously; columns
-// [g*seg_units, (g+1)*seg_units) of every row are read from segment g.  The per-segment source row
-// pointers are staged in LDS (a few hundred bytes) because lanes of one wave may read different segments.
+// Merge tile: whole destination rows of row_units 16-byte units are written contiguously; every row is the
+// concatenation of n_seg column blocks, block g read from segment g.  The per-segment source row pointers (and, when
+// the blocks differ in width, their first columns) are staged in LDS because lanes of one wave may read different
+// segments.
 struct SegLds {
   const uint8_t* base;  // first row of this tile in the segment's source
   uint64_t pitch;
 };
-constexpr uint32_t kMaxSegLds = 64;
-constexpr int kSegLdsBytes = int(kMaxSegLds * sizeof(SegLds));
+using tpx::kMaxSegLds;
+constexpr int kSegLdsBytes = int(kMaxSegLds * sizeof(SegLds) + (kMaxSegLds + 1) * sizeof(uint32_t) + 12);  // 1296
 
 template <int kThreads, int U, bool NTL, bool NTS>
 __device__ __forceinline__ void merge_tile(const tpx_tile& t, const tpx_segment* __restrict__ segs, const uint8_t* const* src_table,
                                            const DstSet& ds, SegLds* lseg) {
   const uint32_t row_units = t.run_units, seg_units = t.seg_units, n_seg = t.n_seg;
-  const bool in_lds = n_seg <= kMaxSegLds;
+  const bool in_lds = n_seg <= kMaxSegLds;  // always so when the widths differ (seg_units == 0)
+  uint32_t* lfirst = reinterpret_cast<uint32_t*>(lseg + kMaxSegLds);  // lfirst[g] = first column of segment g
   if (in_lds) {
     for (uint32_t g = threadIdx.x; g < n_seg; g += kThreads) {
       const tpx_segment sg = segs[t.seg_first + g];
       lseg[g].base = src_table[sg.src_rank] + sg.src_off + t.src_off * sg.src_pitch;  // t.src_off = first row
       lseg[g].pitch = sg.src_pitch;
+      if (!seg_units) {
+        uint32_t first = 0;
+        for (uint32_t k = 0; k < g; ++k) first += segs[t.seg_first + k].units;
+        lfirst[g] = first;
+        if (g + 1 == n_seg) lfirst[n_seg] = first + sg.units;
+      }
     }
     __syncthreads();
   }
   auto src_of = [&](uint32_t idx) -> const v4u* {
     const uint32_t row = idx / row_units;
     const uint32_t c = idx - row * row_units;
-    const uint32_t g = c / seg_units;
-    const uint32_t col = c - g * seg_units;
+    uint32_t g, col;
+    if (seg_units) {
+      g = c / seg_units;
+      col = c - g * seg_units;
+    } else {  // a handful of segments: walk their first columns
+      g = 0;
+      while (c >= lfirst[g + 1]) ++g;
+      col = c - lfirst[g];
+    }
     if (in_lds) return reinterpret_cast<const v4u*>(lseg[g].base + row * lseg[g].pitch + uint64_t(col) * 16);
     const tpx_segment sg = segs[t.seg_first + g];
     return reinterpret_cast<const v4u*>(src_table[sg.src_rank] + sg.src_off + (t.src_off + row) * sg.src_pitch + uint64_t(col) * 16);
@@ -345,6 +360,7 @@ __device__ __forceinline__ void gather_tile(const uint8_t* __restrict__ s, uint8
 }
 
 constexpr int kLdsBytes = int(tpx::kBlockBytes);  // a one-shot block; the general path's sub-tiles are smaller
+constexpr uint32_t kLdsPerCu = 160 * 1024;        // gfx950
 static_assert(kLdsBytes >= TransposeShape<uint8_t>::kBytes && kLdsBytes >= TransposeShape<uint16_t>::kBytes &&
                   kLdsBytes >= TransposeShape<uint32_t>::kBytes && kLdsBytes >= TransposeShape<uint64_t>::kBytes, "LDS budget");
 
@@ -354,7 +370,7 @@ __global__ __launch_bounds__(kThreads) void tpx_execute_tiles(const tpx::Workspa
                                                               const uint32_t* __restrict__ first_tile,
                                                               const uint32_t* __restrict__ coarse,
                                                               const tpx_segment* __restrict__ segs, uint32_t n_boxes,
-                                                              uint32_t n_tiles, uint32_t streams, PtrTable ptrs) {
+                                                              uint32_t n_tiles, uint32_t order, PtrTable ptrs) {
   // dynamic LDS only: the segment table of a merge tile or the staging block of a transposing tile (a workgroup
   // executes one tile, so the two never coexist)
   extern __shared__ __align__(16) uint8_t lds_raw[];
@@ -363,13 +379,24 @@ __global__ __launch_bounds__(kThreads) void tpx_execute_tiles(const tpx::Workspa
   // plan since the upload would send the moves anywhere): otherwise the whole grid does nothing.
   if (header->plan_id != plan_id) return;
   // Locate this workgroup's tile; everything here is uniform for the workgroup, so these are scalar loads.
-  // With `streams` = S > 1 the tile numbers are permuted so that workgroup b works on stream b % S, each
-  // stream being a contiguous 1/S of the tile sequence (gridDim.x is a multiple of S then).  The workgroups
-  // in flight at any moment then touch S distant regions of the rank buffers instead of one, which spreads
-  // the load over HBM channels and banks; all streams advance at the same rate, so they end together.
+  // `order` = S | C << 16.  The tile sequence is cut into S contiguous parts ("streams") that advance side by side, so
+  // the workgroups in flight touch S distant regions of the rank buffers instead of one, which spreads the load over
+  // HBM channels and banks; all streams advance at the same rate, so they end together.
+  // C > 0 (S divides 8): the order is XCD-aware.  Workgroups are dealt round-robin to the 8 XCDs (workgroup b runs on XCD
+  // b % 8), so XCD x serves stream x % S together with the 8/S - 1 other XCDs of that stream, and within the stream
+  // each XCD takes runs of C consecutive tiles: what one XCD has in flight is contiguous in the plan (and mostly in
+  // memory), not every 8th tile.  C = 0: workgroup b simply takes the (b / S)-th tile of stream b % S.
   uint32_t tile_no = blockIdx.x;
-  if (streams > 1) {
-    tile_no = (blockIdx.x % streams) * (gridDim.x / streams) + (blockIdx.x / streams);
+  const uint32_t S = order & 0xffff, C = order >> 16;
+  if (C) {
+    const uint32_t x = blockIdx.x & 7, i = blockIdx.x >> 3, per = 8 / S, stream = x % S, member = x / S;
+    const uint32_t q = (n_tiles + S - 1) / S;  // tiles per stream
+    const uint32_t j = ((i / C) * per + member) * C + i % C;
+    if (j >= q) return;  // slots the grid was rounded up by
+    tile_no = stream * q + j;
+    if (tile_no >= n_tiles) return;
+  } else if (S > 1) {
+    tile_no = (blockIdx.x % S) * (gridDim.x / S) + (blockIdx.x / S);
     if (tile_no >= n_tiles) return;
   }
   const uint32_t box = tpx::find_box(first_tile, coarse, n_boxes, tile_no);
@@ -507,17 +534,35 @@ tpx_status hip_launch_tiles(const void* workspace, const tpx_plan_s& plan, const
   const uint8_t* base = static_cast<const uint8_t*>(workspace);
   const bool automatic = variant == 0;
   if (automatic) {
-    // a workgroup should load its whole tile at once (threads x loads in flight x 16 bytes = tile); a plan with
-    // transposing tiles has 64 KiB tiles and blocks, two workgroups of 512 threads per CU (LDS: 2 x 65 KiB)
-    variant = plan.needs_lds                 ? (3 | 24 | (1 << 5))   //  512 threads x 8
-            : plan.tile_bytes_used >= 131072 ? (3 | 24 | (2 << 5))   // 1024 threads x 8
+    // A workgroup loads its whole tile at once (threads x loads in flight x 16 bytes = tile).  64 KiB tiles (the
+    // default, and what a plan with transposing blocks always has) go to 512 threads x 8 loads; small jobs have smaller
+    // tiles and smaller workgroups; tiles of 128 KiB and more (a plan option) to 1024 threads x 8.
+    variant = plan.tile_bytes_used >= 131072 ? (3 | 24 | (2 << 5))   // 1024 threads x 8
             : plan.tile_bytes_used >= 65536  ? (3 | 24 | (1 << 5))   //  512 threads x 8
                                              : (2 | 24);             //  256 threads x 4 (small jobs, small tiles)
   }
-  // interleaving several parts of the plan pays only when tiles cost the same; a plan that mixes plain and
-  // replicated moves runs in plan order
+  // Workgroups per CU.  The memory side is saturated with about 64 KiB in flight per CU (16 MiB on the chip); more
+  // only lengthens the queues in front of DRAM and costs bandwidth (measured: one 512-thread workgroup with 64 KiB in
+  // flight per CU beats two of them, and one 1024-thread workgroup with 128 KiB, by 2-3 %).  Registers would allow two
+  // 512-thread workgroups, so occupancy is capped through the LDS request: a workgroup that asks for a little more
+  // than half of the CU's 160 KiB has the CU to itself.
+  uint32_t per_cu = uint32_t(tuning().occupancy.load());
+  if (!per_cu && threads_of(variant) == 512) per_cu = 1;
+  uint32_t lds_bytes = plan.needs_lds ? kLdsBytes : kSegLdsBytes;
+  if (per_cu) lds_bytes = std::max<uint32_t>(lds_bytes, ((kLdsPerCu / (per_cu + 1)) & ~255u) + 256);  // per_cu fit, per_cu + 1 do not
+  // Tile order.  Interleaving several parts of the plan pays only when tiles cost the same; a plan that mixes plain
+  // and replicated moves runs as one stream.  Runs of 8 tiles per XCD (see the kernel) unless the plan has transposing
+  // blocks, whose boxes already order their tiles for the destination.
   const uint32_t streams = plan.uniform_tiles ? uint32_t(std::max<uint64_t>(1, tuning().streams.load())) : 1;
-  const uint32_t grid = uint32_t((plan.n_tiles + streams - 1) / streams * streams);
+  uint32_t chunk = uint32_t(tuning().chunk.load());
+  if (!chunk) chunk = plan.needs_lds ? 1 : 8;  // knob: 0 = automatic, 1 = no XCD-aware runs
+  uint32_t grid = uint32_t((plan.n_tiles + streams - 1) / streams * streams);
+  uint32_t order = streams;
+  if (chunk > 1 && 8 % streams == 0) {
+    const uint64_t q = (plan.n_tiles + streams - 1) / streams, unit = uint64_t(8 / streams) * chunk;
+    grid = uint32_t((q + unit - 1) / unit * unit * streams);
+    order = streams | (chunk << 16);
+  }
   KernelFn k = pick_kernel(variant);
   const WorkspaceHeader* a_header = reinterpret_cast<const WorkspaceHeader*>(base + w.header_off);
   uint64_t a_id = plan.id;
@@ -525,11 +570,11 @@ tpx_status hip_launch_tiles(const void* workspace, const tpx_plan_s& plan, const
   const uint32_t* a_first = reinterpret_cast<const uint32_t*>(base + w.first_off);
   const uint32_t* a_coarse = reinterpret_cast<const uint32_t*>(base + w.coarse_off);
   const tpx_segment* a_segs = reinterpret_cast<const tpx_segment*>(base + w.seg_off);
-  uint32_t a_nboxes = uint32_t(plan.flat.size()), a_ntiles = uint32_t(plan.n_tiles), a_streams = streams;
-  void* args[] = {&a_header, &a_id, &a_boxes, &a_first, &a_coarse, &a_segs, &a_nboxes, &a_ntiles, &a_streams, &pt};
+  uint32_t a_nboxes = uint32_t(plan.flat.size()), a_ntiles = uint32_t(plan.n_tiles), a_order = order;
+  void* args[] = {&a_header, &a_id, &a_boxes, &a_first, &a_coarse, &a_segs, &a_nboxes, &a_ntiles, &a_order, &pt};
   // the launch's own status, not the runtime's last-error slot, which other users of the runtime share
   const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(k), dim3(grid), dim3(threads_of(variant)), args,
-                                       plan.needs_lds ? kLdsBytes : kSegLdsBytes, static_cast<hipStream_t>(stream));
+                                       lds_bytes, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return hip_fail(e, "launching the tile kernel");
   return TPX_OK;
 }

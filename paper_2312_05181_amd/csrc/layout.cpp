@@ -35,7 +35,7 @@ Tuning& tuning() {
 }
 
 tpx_status resolve_opts(const tpx_plan_opts* in, tpx_plan_opts& out) {
-  out = tpx_plan_opts{131072, 8, 0};
+  out = tpx_plan_opts{65536, 8, 0};
   if (!in) return TPX_OK;
   if (in->tile_bytes) {
     if (in->tile_bytes < 4096 || in->tile_bytes > 4194304 || (in->tile_bytes & (in->tile_bytes - 1)))

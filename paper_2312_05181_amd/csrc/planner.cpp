@@ -309,21 +309,26 @@ tpx_status tile_boxes(tpx_plan_s& plan, uint64_t tile_bytes) {
     const tpx_box& b = plan.boxes[bi];
     if (box_bytes(b) == 0) continue;
     // merge(W) inside the tile: K consecutive moves that each bring one column block of the same
-    // destination rows (equal widths, together the whole row) become one MERGE box whose tiles write
-    // whole destination rows and read K sources.  Anything irregular keeps one box per move.
-    if (b.kind == TPX_BOX_COPY && b.ndim == 1 && b.run_bytes % 16 == 0 && b.dst_stride[0] % b.run_bytes == 0 &&
-        b.dst_stride[0] > b.run_bytes && b.dst_stride[0] <= tile_bytes && b.extent[0] <= 0xffffffffull) {
-      const uint64_t K = b.dst_stride[0] / b.run_bytes;
-      bool ok = bi + K <= plan.boxes.size() && K <= 0xffff;
-      uint64_t bits = b.dst_off | b.dst_stride[0];
-      for (uint64_t k = 0; ok && k < K; ++k) {
-        const tpx_box& c = plan.boxes[bi + k];
-        ok = c.kind == TPX_BOX_COPY && c.ndim == 1 && c.run_bytes == b.run_bytes && c.extent[0] == b.extent[0] &&
+    // destination rows, together the whole row, become one MERGE box whose tiles write whole destination
+    // rows and read K sources.  The blocks may differ in width (T 3 -> 4 cuts rows in thirds and quarters);
+    // then the kernel needs the segment table in LDS, which bounds K.
+    if (b.kind == TPX_BOX_COPY && b.ndim == 1 && b.run_bytes % 16 == 0 && b.dst_stride[0] > b.run_bytes &&
+        b.dst_stride[0] <= tile_bytes && b.dst_stride[0] % 16 == 0 && b.extent[0] <= 0xffffffffull) {
+      uint64_t K = 0, width = 0, bits = b.dst_off | b.dst_stride[0];
+      bool ok = true, equal = true;
+      while (ok && width < b.dst_stride[0]) {
+        ok = bi + K < plan.boxes.size() && K < 0xffff;
+        if (!ok) break;
+        const tpx_box& c = plan.boxes[bi + K];
+        ok = c.kind == TPX_BOX_COPY && c.ndim == 1 && c.run_bytes % 16 == 0 && c.extent[0] == b.extent[0] &&
              c.dst_stride[0] == b.dst_stride[0] && c.dst_rank == b.dst_rank && c.n_dst == b.n_dst &&
-             c.dst_rank_stride == b.dst_rank_stride && c.dst_off == b.dst_off + k * b.run_bytes &&
-             c.src_rank < TPX_MAX_RANKS;
+             c.dst_rank_stride == b.dst_rank_stride && c.dst_off == b.dst_off + width && c.src_rank < TPX_MAX_RANKS;
         bits |= c.src_off | c.src_stride[0];
+        equal = equal && c.run_bytes == b.run_bytes;
+        width += c.run_bytes;
+        ++K;
       }
+      ok = ok && width == b.dst_stride[0] && K >= 2 && (equal || K <= kMaxSegLds);
       if (ok && bits % 16 == 0) {
         FlatBox f{};
         f.kind = TPX_TILE_MERGE;
@@ -342,10 +347,10 @@ tpx_status tile_boxes(tpx_plan_s& plan, uint64_t tile_bytes) {
         f.rows_per_tile = uint32_t(std::max<uint64_t>(1, tile_bytes / b.dst_stride[0]));
         f.seg_first = uint32_t(plan.segments.size());
         f.n_seg = uint32_t(K);
-        f.seg_units = uint32_t(b.run_bytes / 16);
+        f.seg_units = equal ? uint32_t(b.run_bytes / 16) : 0;
         for (uint64_t k = 0; k < K; ++k) {
           const tpx_box& c = plan.boxes[bi + k];
-          plan.segments.push_back(tpx_segment{c.src_off, c.src_stride[0], c.src_rank, 0});
+          plan.segments.push_back(tpx_segment{c.src_off, c.src_stride[0], c.src_rank, uint32_t(c.run_bytes / 16)});
         }
         plan.flat.push_back(f);
         bi += K - 1;
@@ -477,11 +482,18 @@ tpx_status validate_tiles(tpx_plan_s& plan) {
       if (!plan.side[1].alive[r]) return fail(TPX_ERR_INVALID_ARG, "internal: a move targets a rank that is not to be built");
     }
     if (t.kind == TPX_TILE_MERGE) {
-      if (!t.n_seg || uint64_t(t.n_seg) * t.seg_units != t.run_units || uint64_t(t.seg_first) + t.n_seg > plan.segments.size())
+      if (!t.n_seg || uint64_t(t.seg_first) + t.n_seg > plan.segments.size() || (!t.seg_units && t.n_seg > kMaxSegLds))
         return fail(TPX_ERR_INVALID_ARG, "internal: bad segment range");
+      uint64_t row_units = 0;
       for (uint32_t k = 0; k < t.n_seg; ++k) {
         const tpx_segment& sg = plan.segments[t.seg_first + k];
-        const uint64_t slast = sg.src_off + (t.nrows - 1) * sg.src_pitch + uint64_t(t.seg_units) * unit;
+        if (!sg.units || (t.seg_units && sg.units != t.seg_units)) return fail(TPX_ERR_INVALID_ARG, "internal: bad segment width");
+        row_units += sg.units;
+      }
+      if (row_units != t.run_units) return fail(TPX_ERR_INVALID_ARG, "internal: the segments of a merge do not make up its rows");
+      for (uint32_t k = 0; k < t.n_seg; ++k) {
+        const tpx_segment& sg = plan.segments[t.seg_first + k];
+        const uint64_t slast = sg.src_off + (t.nrows - 1) * sg.src_pitch + uint64_t(sg.units) * unit;
         if (sg.src_rank >= plan.side[0].bytes.size() || slast > plan.side[0].bytes[sg.src_rank])
           return fail(TPX_ERR_INVALID_ARG, "internal: a merge reads outside its source buffer");
       }

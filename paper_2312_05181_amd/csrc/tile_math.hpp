@@ -35,13 +35,14 @@ struct FlatBox {
   uint8_t n_dst;            // the tile is written to buffers dst_rank + k * dst_rank_stride, k < n_dst
   uint8_t dst_rank_stride;
   uint32_t seg_first;       // MERGE boxes: first entry in the segment table, segments per row,
-  uint32_t n_seg;           // units per segment
+  uint32_t n_seg;           // units per segment (0: the segments' widths differ, each has its own)
   uint32_t seg_units;
   uint32_t rows_first;      // tile order inside the box: 0 = along a row of tiles first, 1 = down a column of tiles first
 };
 static_assert(sizeof(FlatBox) == 96, "FlatBox layout");
 
 constexpr uint32_t kCoarseShift = 6;  // one coarse entry per 64 tiles
+constexpr uint32_t kMaxSegLds = 64;    // segments of a merge box whose table the kernel can stage in LDS
 
 // Transposing tiles that the kernel moves in one shot (whole tile in flight, staged once through LDS) are
 // kBlockBytes large.  For an element of eb bytes the planner cuts a transposing move into blocks of

@@ -102,7 +102,9 @@ tpx_status build_side(const tpx_model& m, const tpx_parallel& par, Side& out);
 // execute: each read sees the old or the new value, never a torn one.
 struct Tuning {
   std::atomic<uint64_t> streams{4};        // tile order: workgroup b works on contiguous part b % streams of the plan
-  std::atomic<uint64_t> variant{0};        // 0 = chosen from the tile size (1024 threads x 8 nontemporal loads for 128 KiB tiles)
+  std::atomic<uint64_t> chunk{0};          // tile order: tiles an XCD takes in a row (0 = automatic, 1 = none)
+  std::atomic<uint64_t> occupancy{0};      // workgroups per CU, capped through the LDS request (0 = automatic)
+  std::atomic<uint64_t> variant{0};        // 0 = chosen from the tile size (512 threads x 8 nontemporal loads for 64 KiB tiles)
 };
 Tuning& tuning();
 
@@ -122,7 +124,7 @@ struct tpx_plan_s {
   tpx_stats_t stats{};
   bool needs_lds = false;       // some tile is staged through LDS
   bool uniform_tiles = true;    // every tile has the same number of destinations (same cost per byte)
-  tpx_plan_opts opts{131072, 8, 0};  // the caller's options with defaults filled in
+  tpx_plan_opts opts{65536, 8, 0};  // the caller's options with defaults filled in
   uint64_t id = 0;              // process-unique, never 0: stamps the workspace header
   std::vector<uint8_t> image;   // host image of the whole workspace (header and tables), what an upload copies
 };

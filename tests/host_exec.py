@@ -32,21 +32,24 @@ def run_tiles(plan, src_bufs, dst_bufs, cover=None):
     for t in plan.tiles():
         unit = 1 << t.unit_log2
         if t.kind == B.TILE_MERGE:
-            # whole destination rows; column block k of every row comes from segment seg_first + k
+            # whole destination rows; column block g of every row comes from segment seg_first + g
             row0 = int(t.src_off)
+            widths = [segs[t.seg_first + g].units for g in range(t.n_seg)]
+            assert sum(widths) == t.run_units and (t.seg_units == 0 or all(w == t.seg_units for w in widths))
             i = np.arange(t.nrows, dtype=np.int64)[:, None, None]
-            j = np.arange(t.seg_units, dtype=np.int64)[None, :, None]
             kk = np.arange(unit, dtype=np.int64)[None, None, :]
-            assert t.n_seg * t.seg_units == t.run_units
             for c in range(t.n_dst):
                 r = t.dst_rank + c * t.dst_rank_stride
+                first = 0
                 for g in range(t.n_seg):
                     sg = segs[t.seg_first + g]
+                    j = np.arange(widths[g], dtype=np.int64)[None, :, None]
                     si = (int(sg.src_off) + (row0 + i) * int(sg.src_pitch) + j * unit + kk).reshape(-1)
-                    di = (int(t.dst_off) + i * int(t.dst_pitch) + (g * t.seg_units + j) * unit + kk).reshape(-1)
+                    di = (int(t.dst_off) + i * int(t.dst_pitch) + (first + j) * unit + kk).reshape(-1)
                     dst_bufs[r][di] = src_bufs[sg.src_rank][si]
                     if cover is not None:
                         np.add.at(cover[r], di, 1)
+                    first += widths[g]
             continue
         i = np.arange(t.nrows, dtype=np.int64)[:, None, None]
         j = np.arange(t.run_units, dtype=np.int64)[None, :, None]

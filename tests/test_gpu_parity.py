@@ -542,6 +542,23 @@ def test_shared_reads_eight_way_multicast(cuda):
 
 
 MID = Model(n_layers=2, hidden=512, n_heads=8, ffn=2048, vocab_true=4096, max_pos=64)
+TWELVE = Model(n_layers=2, hidden=192, n_heads=12, ffn=768, vocab_true=1536, max_pos=16)
+
+
+@pytest.mark.parametrize("src,dst", [(Parallel(3, 1, 1), Parallel(4, 1, 1)), (Parallel(4, 1, 1), Parallel(3, 2, 1)),
+                                     (Parallel(6, 1, 1), Parallel(4, 1, 2)), (Parallel(12, 1, 1), Parallel(2, 1, 1)),
+                                     (Parallel(6, 2, 1), Parallel(4, 1, 1, qkv_layout=1))])
+def test_merges_of_unequal_column_blocks(cuda, src, dst):
+    """Thirds into quarters and the like: a new row of a row-parallel weight is made of column blocks of different widths,
+    merged inside the tile (every segment with its own width), also as a multicast move."""
+    print("case", src, dst, flush=True)
+    plan = _check_small(TWELVE, synth.MIX_GPT, src, dst, seed=31, opts=dict(tile_bytes=16384))
+    merges = [t for t in plan.tiles() if t.kind == tpx.binding.TILE_MERGE]
+    if src.T % dst.T == 0:         # 12 -> 2: six equal blocks per row
+        assert merges and all(t.seg_units * t.n_seg == t.run_units for t in merges)
+    else:
+        assert any(t.seg_units == 0 for t in merges)
+
 
 
 @pytest.mark.parametrize("src,dst", [
@@ -559,18 +576,34 @@ def test_transposed_storage_mid_size(cuda, src, dst):
     assert 2 in kinds        # TPX_BOX_TRANSPOSE
 
 
-@pytest.mark.parametrize("streams", [1, 3, 4, 7, 8, 64, 1000])
-def test_tile_order_streams(cuda, streams):
-    """Any tile order gives the same bytes, also when the tile count is not a multiple of the stream count
-    or smaller than it (the surplus workgroups exit)."""
-    print("streams", streams, flush=True)
+@pytest.mark.parametrize("chunk", [0, 1, 3, 8, 100])
+@pytest.mark.parametrize("streams", [1, 2, 3, 4, 7, 8, 64, 1000])
+def test_tile_order_streams(cuda, streams, chunk):
+    """Any tile order gives the same bytes: streams that do or do not divide the tile count or the 8 XCDs, more streams
+    than tiles, XCD-aware runs of any length (the surplus workgroups of the rounded-up grid exit)."""
+    print("streams", streams, "chunk", chunk, flush=True)
     tpx.tpx_set_option("streams", streams)
+    tpx.tpx_set_option("chunk", chunk)
     try:
         plan = _check_small(WIDE, synth.MIX_GPT, Parallel(4, 1, 1), Parallel(2, 2, 1), opts=dict(tile_bytes=8192))
         assert plan.num_tiles() % 7 != 0 or plan.num_tiles() % 64 != 0
         _check_small(SMALL, SMALL_MIX, Parallel(2, 1, 1), Parallel(1, 1, 1), opts=dict(tile_bytes=8192))
+        _check_small(SMALL, SMALL_MIX, Parallel(2, 2, 1), Parallel(2, 2, 3), opts=dict(tile_bytes=4096))      # mixed plan: one stream
     finally:
         tpx.tpx_set_option("streams", 4)
+        tpx.tpx_set_option("chunk", 0)
+
+
+@pytest.mark.parametrize("occupancy", [1, 2, 3, 16])
+def test_occupancy_cap(cuda, occupancy):
+    """Workgroups per CU are capped through the LDS request; the bytes moved do not depend on it (copy, merge and
+    transposing tiles, default 64 KiB tiles and 512-thread workgroups)."""
+    tpx.tpx_set_option("occupancy", occupancy)
+    try:
+        _check_small(MID, synth.MIX_GPT, Parallel(4, 1, 1), Parallel(2, 2, 1), seed=23, opts=dict(tile_bytes=65536))
+        _check_small(MID, synth.MIX_GPT, Parallel(2, 1, 1), Parallel(4, 1, 1, w_transposed=1), seed=23)
+    finally:
+        tpx.tpx_set_option("occupancy", 0)
 
 
 def test_execute_inside_a_hip_graph(cuda):

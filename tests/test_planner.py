@@ -409,6 +409,8 @@ def test_error_codes():
     assert st(lambda: tpx.tpx_set_option("no_such_option", 1)) == B.TPX_ERR_INVALID_ARG
     assert st(lambda: tpx.tpx_set_option("tile_bytes", 4096)) == B.TPX_ERR_INVALID_ARG      # a plan option, not a knob
     assert st(lambda: tpx.tpx_set_option("streams", 0)) == B.TPX_ERR_INVALID_ARG
+    assert st(lambda: tpx.tpx_set_option("chunk", 5000)) == B.TPX_ERR_INVALID_ARG
+    assert st(lambda: tpx.tpx_set_option("occupancy", 17)) == B.TPX_ERR_INVALID_ARG
     one = dict(T=1, P=1, D=1)
     for bad_opts in (dict(tile_bytes=5000), dict(tile_bytes=2048), dict(max_multicast=129), dict(share_reads=2), dict(tiles=1)):
         assert st(lambda: tpx.tpx_plan(m, one, one, bad_opts)) == B.TPX_ERR_INVALID_ARG
@@ -457,9 +459,21 @@ def test_row_parallel_merges_become_merge_tiles():
             assert t.n_seg == 8 and t.n_seg * t.seg_units == t.run_units and t.dst_pitch == t.run_units * 16
             merge_bytes += 1
     assert merge_bytes > 500
-    # a 3 -> 4 re-slicing has unequal pieces per destination row: those stay one tile per move
+    # a 3 -> 4 re-slicing has unequal pieces per destination row (thirds against quarters, in twelfths: new quarter 1 = 1 + 2,
+    # quarter 2 = 2 + 1): those merges carry each segment's own width; quarters 0 and 3 lie inside one third (plain copies)
     model5, src5, dst5, _, _ = H.CONFIGS[5]
-    assert len(plan_for(model5, src5, dst5).segments()) == 0
+    plan5 = plan_for(model5, src5, dst5)
+    segs5 = plan5.segments()
+    assert len(segs5) == model5.n_layers * len(model5.state_elem_bytes) * 2 * 2 * 2     # 2 weights x 2 middle quarters x 2 pieces
+    irregular = 0
+    for i in range(0, plan5.num_tiles(), 53):
+        t = B.tpx_tile()
+        B._check(B._lib.tpx_get_tile(plan5._h, i, t))
+        if t.kind == B.TILE_MERGE:
+            w = [segs5[t.seg_first + g].units for g in range(t.n_seg)]
+            assert t.seg_units == 0 and t.n_seg == 2 and sum(w) == t.run_units and sorted(w) == [t.run_units // 3, 2 * t.run_units // 3]
+            irregular += 1
+    assert irregular > 100
 
 
 def test_command_line_front_end():

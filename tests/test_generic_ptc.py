@@ -332,6 +332,38 @@ def _collection_of(plan, side):
     return out
 
 
+BIG = {
+    # expert parallelism at the size of a small mixture-of-experts layer stack: 8 or 16 experts of two 4096 x 1024 matrices,
+    # four state kinds (14 bytes per parameter): 0.9 and 1.9 GB; sequence parallelism on a [8, 4096, 4096] bf16 activation: 268 MB;
+    # a 2-D grid of a [8192, 6144] tensor (bf16 + fp32)
+    "experts ep8 -> ep4 x tp2": lambda: (experts(8, n_experts=8, h=1024, f=4096), experts(8, tp=2, n_experts=8, h=1024, f=4096)),
+    "experts ep4 x tp4 -> ep16": lambda: (experts(16, tp=4, n_experts=16, h=1024, f=4096), experts(16, n_experts=16, h=1024, f=4096)),
+    "sequence 8 -> 6": lambda: (sequence(8, batch=8, seq=4096, hidden=4096), sequence(6, batch=8, seq=4096, hidden=4096)),
+    "2-D grid 4x2 -> 2x6": lambda: (grid2d(4, 2, shape=(8192, 6144)), grid2d(2, 6, shape=(8192, 6144))),
+}
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name", list(BIG))
+def test_generic_collections_at_scale_gpu(cuda, name):
+    """Expert-, sequence- and grid-parallel collections large enough for the default launch shape (64 KiB tiles, merge tiles,
+    thousands of workgroups): every destination buffer equals the generic oracle's, byte for byte, and the value function."""
+    from tests import gpu_util as G
+    print("case", name, flush=True)
+    src, dst = BIG[name]()
+    a = src_buffers(src, 19)
+    want = oreshard.reshard_ptc(src, dst, H.np_bufs(a), threads=8)
+    plan = plan_of(src, dst)
+    assert plan.num_tiles() > 2000
+    got, _ = G.execute(plan, [x.cuda() for x in a])
+    torch.cuda.synchronize()
+    exact = closed_form(dst, 19)
+    for r in range(len(dst)):
+        have = got[r].cpu()
+        assert np.array_equal(have.numpy(), want[r]), r
+        assert torch.equal(have, exact[r]), r
+
+
 def test_json_configuration_importer():
     """Two per-GPU JSON documents (paper section 5.1) describing a two-matrix model under 2-way tensor
     parallelism and under 1 GPU; the imported collections re-partition like the oracle says."""

@@ -135,6 +135,12 @@ def main() -> int:
     ap.add_argument("--tile-bytes", type=int, default=0)
     ap.add_argument("--variant", type=int, default=-1)
     ap.add_argument("--streams", type=int, default=0)
+    ap.add_argument("--chunk", type=int, default=-1, help="executor knob: tiles an XCD takes in a row (0 = automatic)")
+    ap.add_argument("--occupancy", type=int, default=-1, help="executor knob: workgroups per CU (0 = automatic)")
+    ap.add_argument("--ab", default=None, metavar="CFG;CFG;...",
+                    help="compare settings inside ONE process on fixed buffers (differences between processes are larger than most "
+                         "effects): each CFG is a comma list of key=value with keys streams, chunk, occupancy, variant (executor "
+                         "knobs) and tile_bytes, max_multicast, share_reads (plan options); prints one JSON line")
     ap.add_argument("--no-probe", action="store_true")
     ap.add_argument("--share-reads", action="store_true",
                     help="plan with the share_reads option: replicas of a group are all written from one read")
@@ -160,7 +166,13 @@ def main() -> int:
         tpx.tpx_set_option("variant", args.variant)
     if args.streams:
         tpx.tpx_set_option("streams", args.streams)
+    if args.chunk >= 0:
+        tpx.tpx_set_option("chunk", args.chunk)
+    if args.occupancy >= 0:
+        tpx.tpx_set_option("occupancy", args.occupancy)
     args.opts = dict(tile_bytes=args.tile_bytes, share_reads=int(args.share_reads))
+    if args.ab:
+        return ab_compare(args)
 
     if args.workload == DATASET_WORKLOAD:
         return bench_dataset(args)
@@ -292,6 +304,74 @@ def main() -> int:
         "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
+    return 0
+
+
+PLAN_KEYS = ("tile_bytes", "max_multicast", "share_reads")
+KNOB_DEFAULTS = {"streams": 4, "chunk": 0, "occupancy": 0, "variant": 0}
+
+
+def ab_compare(args) -> int:
+    """A/B/A comparison of executor knobs and plan options on one workload, inside one process: every setting runs on
+    the same source and destination buffers (so on the same physical pages), in three interleaved rounds of six launches,
+    timed with HIP events.  Reports bytes moved per second per round for every setting."""
+    import torch
+
+    import paper_2312_05181_amd as tpx
+
+    cfgs = []
+    for text in args.ab.split(";"):
+        cfg = dict((kv.split("=")[0].strip(), int(kv.split("=")[1])) for kv in text.split(",") if kv.strip())
+        unknown = set(cfg) - set(PLAN_KEYS) - set(KNOB_DEFAULTS)
+        if unknown:
+            print(f"bench.py --ab: unknown key {sorted(unknown)[0]}", file=sys.stderr)
+            return 2
+        cfgs.append((text.strip() or "default", cfg))
+
+    def make_plan(cfg):
+        opts = dict(args.opts)
+        opts.update({k: v for k, v in cfg.items() if k in PLAN_KEYS})
+        if args.workload == DATASET_WORKLOAD:
+            c = DATASET_CFG
+            cur = [c["steps_done"] * (c["global_batch"] // c["D_src"])] * c["D_src"]
+            return tpx.tpx_plan_dataset(c["n_samples"], c["global_batch"], c["D_src"], c["D_dst"], cur, opts=opts)
+        model, src, dst, _, _ = WORKLOADS[args.workload]
+        return tpx.tpx_plan(model, src, dst, opts)
+
+    plans = [make_plan(cfg) for _, cfg in cfgs]
+    p0 = plans[0]
+    src_bufs = [torch.full((max(1, p0.buffer_bytes(0, r)),), r + 1, dtype=torch.uint8, device="cuda") for r in range(p0.num_buffers(0))]
+    dst_bufs = [torch.zeros(max(1, p0.buffer_bytes(1, r)), dtype=torch.uint8, device="cuda") for r in range(p0.num_buffers(1))]
+    ws = torch.empty(max(p.workspace_bytes() for p in plans), dtype=torch.uint8, device="cuda")
+    sp, dp = [b.data_ptr() for b in src_bufs], [b.data_ptr() for b in dst_bufs]
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def timed(plan, cfg, launches=6):
+        for key, default in KNOB_DEFAULTS.items():
+            tpx.tpx_set_option(key, cfg.get(key, default))
+        tpx.tpx_workspace_forget(ws.data_ptr())
+        for _ in range(2):
+            plan.execute(sp, dp, ws.data_ptr(), stream)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(launches):
+            plan.execute(sp, dp, ws.data_ptr(), stream)
+        e1.record()
+        torch.cuda.synchronize()
+        st = plan.stats()
+        return (st["bytes_read"] + st["bytes_written"]) / (e0.elapsed_time(e1) / launches * 1e-3) / 1e9
+
+    rounds = [[] for _ in cfgs]
+    for _ in range(3):
+        for i, ((_, cfg), plan) in enumerate(zip(cfgs, plans)):
+            rounds[i].append(round(timed(plan, cfg), 1))
+    for key, default in KNOB_DEFAULTS.items():
+        tpx.tpx_set_option(key, default)
+    print(json.dumps({"workload": args.workload, "unit": "GB/s", "peak": HBM_PEAK_GBPS,
+                      "settings": [{"setting": name, "n_tiles": plan.stats()["n_tiles"], "rounds": r, "best": max(r),
+                                    "pct_of_hbm_peak": round(100 * max(r) / HBM_PEAK_GBPS, 2)}
+                                   for (name, _), plan, r in zip(cfgs, plans, rounds)]}), flush=True)
     return 0
 
 

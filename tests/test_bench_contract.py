@@ -68,6 +68,19 @@ def test_bench_prints_one_json_line_with_the_contract_fields(cuda, workload):
 
 
 @pytest.mark.gpu
+def test_bench_in_process_comparison_mode(cuda):
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--workload", "tiny_2L_h256_(2,1,1)->(4,2,1)", "--ab",
+                        ";streams=1,chunk=1;tile_bytes=4096,occupancy=2"], capture_output=True, text=True, cwd=ROOT, timeout=300)
+    assert r.returncode == 0, r.stderr[-2000:]
+    d = json.loads([l for l in r.stdout.splitlines() if l.strip()][-1])
+    assert [x["setting"] for x in d["settings"]] == ["default", "streams=1,chunk=1", "tile_bytes=4096,occupancy=2"]
+    assert all(len(x["rounds"]) == 3 and x["best"] > 0 for x in d["settings"])
+    assert d["settings"][2]["n_tiles"] > d["settings"][0]["n_tiles"]
+    bad = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--ab", "nonsense=1"], capture_output=True, text=True, cwd=ROOT)
+    assert bad.returncode != 0 and "unknown key" in bad.stderr
+
+
+@pytest.mark.gpu
 def test_c_abi_without_python_or_torch(cuda):
     """paper_2312_05181_amd/examples/reshard_selftest.cpp, built next to the library: plans, executes and checks a reshard through the
     C ABI alone, with the system's HIP runtime."""

@@ -364,6 +364,54 @@ def test_generic_collections_at_scale_gpu(cuda, name):
         assert torch.equal(have, exact[r]), r
 
 
+def _long_run_pair(n, eb, kind):
+    """One rank on either side; a small tensor changes place with a long one, so the long one moves as a single contiguous run
+    between different offsets."""
+    small = (1, 1, 4, (64,), (0,), (64,), (0,))
+    big = (0, kind, eb, (n,), (0,), (n,), (0,))
+    return pack([[small, big]]), pack([[big, small]])
+
+
+def test_contiguous_run_beyond_32_bit_unit_counts():
+    """A single contiguous move of 40 GiB + 1 bytes (so 1-byte units, twenty times what a 32-bit count of units holds) is planned
+    as consecutive tiles that cover it exactly once, source and destination advancing together."""
+    import ctypes as C
+    n = 40 * (1 << 30) + 1
+    src, dst = _long_run_pair(n, 1, 0)
+    plan = plan_of(src, dst)
+    st = plan.stats()
+    assert st["bytes_read"] == st["bytes_written"] == n + 256 and st["n_boxes"] == 2
+    tile, pos, seen_small = B.tpx_tile(), 0, 0
+    for i in range(plan.num_tiles()):
+        assert B._lib.tpx_get_tile(plan._h, i, C.byref(tile)) == 0
+        nbytes = tile.nrows * (tile.run_units << tile.unit_log2)
+        if tile.src_off == 0:                      # the small tensor: first on the source, last on the destination
+            assert tile.dst_off == dst[0][0][1].offset and nbytes == 256
+            seen_small += 1
+            continue
+        assert tile.nrows == 1 and tile.src_off == 256 + pos and tile.dst_off == pos and 0 < nbytes <= 65536, i
+        pos += nbytes
+    assert pos == n and seen_small == 1
+
+
+@pytest.mark.gpu
+def test_contiguous_run_beyond_32_bit_unit_counts_gpu(cuda):
+    """2^31 + 12,345 two-byte elements in one move: an odd count, so the unit is 2 bytes and the run exceeds 2^31 units; the
+    kernel's result equals the generic oracle's and the value function, byte for byte."""
+    from tests import gpu_util as G
+    n = (1 << 31) + 12345
+    src, dst = _long_run_pair(n, 2, 0)
+    plan = plan_of(src, dst)
+    assert {t.unit_log2 for t in (plan.tiles()[0], plan.tiles()[-2])} == {1}
+    a = G.alloc(src[0][1], H.SRC_GAP)
+    synth.fill_buffer(a, [H.desc_of(e) for e in src[0][0]], 23, MIX)
+    got, _ = G.execute(plan, [a])
+    torch.cuda.synchronize()
+    assert synth.count_mismatch(got[0], [H.desc_of(e) for e in dst[0][0]], 23, MIX) == 0
+    want = oreshard.reshard_ptc(src, dst, [a.cpu().numpy()], threads=8)
+    assert np.array_equal(got[0].cpu().numpy(), want[0])
+
+
 def test_json_configuration_importer():
     """Two per-GPU JSON documents (paper section 5.1) describing a two-matrix model under 2-way tensor
     parallelism and under 1 GPU; the imported collections re-partition like the oracle says."""

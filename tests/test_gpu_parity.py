@@ -480,6 +480,17 @@ def test_paper_reconfiguration_pairs(cuda, name):
     _run_full_size(name, model, src, dst, seed, plan)
 
 
+def test_single_rank_redeploy_moves_one_whole_buffer(cuda):
+    """6.7B shape on one rank, redeployed to one rank (section 6.3's redeployment at T = P = D = 1): the whole 93 GB buffer
+    coalesces into a single contiguous move, longer than a 32-bit count of 16-byte units, which the planner cuts into
+    several runs of tiles."""
+    model, src, dst = H.GPT_6_7B, Parallel(1, 1, 1), Parallel(1, 1, 1)
+    plan = plan_for(model, src, dst)
+    st = plan.stats()
+    assert st["n_boxes"] == 1 and st["bytes_read"] == st["bytes_written"] == 93_161_635_840
+    _run_full_size("gpt6.7b_(1,1,1)->(1,1,1)", model, src, dst, 4, plan)
+
+
 def _layout_pairs():
     import bench
     return list(bench.LAYOUT_PAIRS)

@@ -430,24 +430,27 @@ tpx_status tile_boxes(tpx_plan_s& plan, uint64_t tile_bytes) {
     }
     // A contiguous run longer than 32-bit unit counts reach (a whole arena of one rank coalesced into one move)
     // is cut into several flat boxes, each a whole number of chunks long.
+    // The same goes for more rows than a 32-bit count holds: several flat boxes of whole tiles of rows.
     const bool linear = f.kind == TPX_TILE_COPY || f.kind == TPX_TILE_FILL;
     const uint64_t piece = linear ? (kMaxRunUnits / f.chunk_units) * f.chunk_units : 0xffffffffull;
-    if (nI > 0xffffffffull || (!linear && nJ > piece)) return fail(TPX_ERR_INVALID_ARG, "a move is too large for 32-bit tile indices");
-    f.nrows = uint32_t(nI);
+    const uint64_t row_piece = linear ? (kMaxRunUnits / f.rows_per_tile) * f.rows_per_tile : 0xffffffffull;
+    if (!linear && (nI > row_piece || nJ > piece)) return fail(TPX_ERR_INVALID_ARG, "a transposing move is too large for 32-bit tile indices");
     uint64_t idx[4] = {0, 0, 0, 0};
     for (;;) {  // odometer over the enumerated axes
       f.src_off = b.src_off;
       f.dst_off = b.dst_off;
       for (uint32_t k = 0; k < b.ndim; ++k)
         if (k != I && k != J) { f.src_off += idx[k] * b.src_stride[k]; f.dst_off += idx[k] * b.dst_stride[k]; }
-      for (uint64_t j0 = 0; j0 < nJ; j0 += piece) {
-        FlatBox g = f;
-        g.run_units = uint32_t(std::min<uint64_t>(piece, nJ - j0));
-        g.chunks_per_row = (g.run_units + g.chunk_units - 1) / g.chunk_units;
-        g.src_off += j0 * f.src_step;
-        g.dst_off += j0 * f.dst_step;
-        plan.flat.push_back(g);
-      }
+      for (uint64_t i0 = 0; i0 < nI; i0 += row_piece)
+        for (uint64_t j0 = 0; j0 < nJ; j0 += piece) {
+          FlatBox g = f;
+          g.nrows = uint32_t(std::min<uint64_t>(row_piece, nI - i0));
+          g.run_units = uint32_t(std::min<uint64_t>(piece, nJ - j0));
+          g.chunks_per_row = (g.run_units + g.chunk_units - 1) / g.chunk_units;
+          g.src_off += i0 * f.src_pitch + j0 * f.src_step;
+          g.dst_off += i0 * f.dst_pitch + j0 * f.dst_step;
+          plan.flat.push_back(g);
+        }
       int k = int(b.ndim) - 1;
       for (; k >= 0; --k) {
         if (uint32_t(k) == I || uint32_t(k) == J) continue;

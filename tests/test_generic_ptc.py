@@ -394,6 +394,25 @@ def test_contiguous_run_beyond_32_bit_unit_counts():
     assert pos == n and seen_small == 1
 
 
+def test_more_rows_than_a_32_bit_count():
+    """A [5*10^9, 32] byte tensor held whole by one rank, cut by columns for two ranks: each destination is one move of 5*10^9
+    rows of 16 bytes (pitch 32 on the source, 16 on the destination); the tiles cover every row once, in order."""
+    import ctypes as C
+    n = 5 * 10 ** 9
+    src = pack([[(0, 0, 1, (n, 32), (0, 0), (n, 32), (0, 1))]])
+    dst = pack([[(0, 0, 1, (n, 32), (0, 16 * j), (n, 16 * j + 16), (0, 1))] for j in range(2)])
+    plan = plan_of(src, dst, opts=dict(tile_bytes=1 << 20))
+    assert plan.stats()["bytes_written"] == 32 * n
+    tile, rows = B.tpx_tile(), [0, 0]
+    for i in range(plan.num_tiles()):
+        assert B._lib.tpx_get_tile(plan._h, i, C.byref(tile)) == 0
+        j = tile.dst_rank
+        assert (tile.src_off, tile.dst_off, tile.src_pitch, tile.dst_pitch) == (32 * rows[j] + 16 * j, 16 * rows[j], 32, 16), i
+        assert tile.run_units << tile.unit_log2 == 16 and 0 < tile.nrows <= 65536
+        rows[j] += tile.nrows
+    assert rows == [n, n]
+
+
 @pytest.mark.gpu
 def test_contiguous_run_beyond_32_bit_unit_counts_gpu(cuda):
     """2^31 + 12,345 two-byte elements in one move: an odd count, so the unit is 2 bytes and the run exceeds 2^31 units; the

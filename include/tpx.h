@@ -23,6 +23,12 @@
  *   - a call returns TPX_OK or a negative tpx_status, never throws or aborts;
  *     out-parameters are untouched on error; tpx_last_error() returns a
  *     thread-local description of the last failure on the calling thread.
+ *
+ * Limits: TPX_MAX_RANKS buffers per side; 2^31 tiles per plan (at the default
+ * 64 KiB per tile far more than one GPU's memory holds); a move may be as long
+ * as a buffer, except that a move between different storage orders may not
+ * exceed 2^32 - 1 elements along either axis of the plane it transposes.  A
+ * plan beyond these is refused with INVALID_ARG.
  */
 #ifndef TPX_H
 #define TPX_H

@@ -140,7 +140,8 @@ def main() -> int:
     ap.add_argument("--ab", default=None, metavar="CFG;CFG;...",
                     help="compare settings inside ONE process on fixed buffers (differences between processes are larger than most "
                          "effects): each CFG is a comma list of key=value with keys streams, chunk, occupancy, variant (executor "
-                         "knobs) and tile_bytes, max_multicast, share_reads (plan options); prints one JSON line")
+                         "knobs), tile_bytes, max_multicast, share_reads (plan options) and dst_shift_kib (all buffers of a side in one "
+                         "allocation, the destination side moved by that many KiB); prints one JSON line")
     ap.add_argument("--no-probe", action="store_true")
     ap.add_argument("--share-reads", action="store_true",
                     help="plan with the share_reads option: replicas of a group are all written from one read")
@@ -315,7 +316,8 @@ KNOB_DEFAULTS = {"streams": 4, "chunk": 0, "occupancy": 0, "variant": 0}
 def ab_compare(args) -> int:
     """A/B/A comparison of executor knobs and plan options on one workload, inside one process: every setting runs on
     the same source and destination buffers (so on the same physical pages), in three interleaved rounds of six launches,
-    timed with HIP events.  Reports bytes moved per second per round for every setting."""
+    timed with HIP events.  Reports bytes moved per second per round for every setting.  Settings are tpx_plan_opts
+    fields, tpx_set_option keys and dst_shift_kib (see below: where the destination buffers sit relative to the sources)."""
     import torch
 
     import paper_2312_05181_amd as tpx
@@ -323,7 +325,7 @@ def ab_compare(args) -> int:
     cfgs = []
     for text in args.ab.split(";"):
         cfg = dict((kv.split("=")[0].strip(), int(kv.split("=")[1])) for kv in text.split(",") if kv.strip())
-        unknown = set(cfg) - set(PLAN_KEYS) - set(KNOB_DEFAULTS)
+        unknown = set(cfg) - set(PLAN_KEYS) - set(KNOB_DEFAULTS) - {"dst_shift_kib"}
         if unknown:
             print(f"bench.py --ab: unknown key {sorted(unknown)[0]}", file=sys.stderr)
             return 2
@@ -346,10 +348,32 @@ def ab_compare(args) -> int:
     ws = torch.empty(max(p.workspace_bytes() for p in plans), dtype=torch.uint8, device="cuda")
     sp, dp = [b.data_ptr() for b in src_bufs], [b.data_ptr() for b in dst_bufs]
     stream = torch.cuda.current_stream().cuda_stream
+    shifts = [cfg.get("dst_shift_kib", 0) << 10 for _, cfg in cfgs]
+    if any(shifts):
+        # placement study: all rank buffers of a side inside one allocation, each at a 2 MiB boundary, and the destination
+        # side as a whole moved by the setting's shift (a multiple of 16 bytes, as tpx_execute requires)
+        del src_bufs, dst_bufs
+        mib2 = 1 << 21
+
+        def arena(side, extra):
+            offs, off = [], 0
+            for r in range(p0.num_buffers(side)):
+                offs.append(off)
+                off = (off + p0.buffer_bytes(side, r) + mib2 - 1) // mib2 * mib2
+            mem = torch.full((off + extra + mib2,), 1 + side, dtype=torch.uint8, device="cuda")
+            base = (mem.data_ptr() + mib2 - 1) // mib2 * mib2
+            return mem, [base + o for o in offs]
+        src_mem, sp = arena(0, 0)
+        dst_mem, dp0 = arena(1, max(shifts))
 
     def timed(plan, cfg, launches=6):
+        nonlocal dp
         for key, default in KNOB_DEFAULTS.items():
             tpx.tpx_set_option(key, cfg.get(key, default))
+        if any(shifts):
+            if (cfg.get("dst_shift_kib", 0) << 10) % 16:
+                raise SystemExit("dst_shift_kib must give a multiple of 16 bytes")
+            dp = [q + (cfg.get("dst_shift_kib", 0) << 10) for q in dp0]
         tpx.tpx_workspace_forget(ws.data_ptr())
         for _ in range(2):
             plan.execute(sp, dp, ws.data_ptr(), stream)

@@ -318,6 +318,22 @@ def test_full_size_workload(cuda, cfg):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("cfg,tile_bytes,variant", [(2, 1 << 18, 0), (2, 1 << 22, 0), (5, 1 << 20, 0), (2, 1 << 20, 26)])
+def test_full_size_with_tiles_of_several_passes(cuda, cfg, tile_bytes, variant):
+    """Tiles larger than what a workgroup holds in flight (256 KiB to 2 MiB against 128 KiB at most; with the smallest
+    kernel shape, 256 threads x 4 loads, 64 passes per tile), on jobs large enough that the planner keeps them: copies,
+    equal merges (workload 2) and merges of unequal column blocks with fills (workload 5)."""
+    model, src, dst, _, seed = H.CONFIGS[cfg]
+    plan = plan_for(model, src, dst, opts=dict(tile_bytes=tile_bytes))
+    biggest = max(t.nrows * (t.run_units << t.unit_log2) for t in plan.tiles()[::97])
+    assert biggest > (1 << 17) and biggest <= tile_bytes
+    tpx.tpx_set_option("variant", variant)
+    try:
+        _run_full_size(f"workload {cfg}, tiles of up to {tile_bytes} bytes, variant {variant}", model, src, dst, seed, plan)
+    finally:
+        tpx.tpx_set_option("variant", 0)
+
+
 @pytest.mark.parametrize("cfg", [2, 5])
 def test_full_size_round_trip_and_composition(cuda, cfg):
     """Properties that hold at any size, in the launch configuration the benchmark times: A -> B -> A gives

@@ -568,6 +568,17 @@ def test_shared_reads_eight_way_multicast(cuda):
     assert sorted({b.n_dst for b in plan.boxes()}) == [2, 3]           # 8 replicas as 3 + 3 + 2
 
 
+def test_multicast_to_the_largest_replica_count(cuda):
+    """One source replica copied to 128 (and, with two tensor-parallel ranks, 2 x 64) new replicas: with max_multicast at its
+    limit every piece is one move with 128 (64) destinations, with 5 the replicas are served in groups of 5 and a rest."""
+    plan = _check_small(SMALL, SMALL_MIX, Parallel(1, 1, 1), Parallel(1, 1, 128), opts=dict(max_multicast=128))
+    assert {b.n_dst for b in plan.boxes()} == {128} and plan.stats()["bytes_written"] == 128 * plan.stats()["bytes_read"]
+    plan = _check_small(SMALL, SMALL_MIX, Parallel(2, 1, 1), Parallel(2, 1, 64, w_transposed=1), opts=dict(max_multicast=128))
+    assert {(b.n_dst, b.dst_rank_stride) for b in plan.boxes()} == {(64, 2)}
+    plan = _check_small(SMALL, SMALL_MIX, Parallel(1, 1, 1), Parallel(1, 1, 128), opts=dict(max_multicast=5))
+    assert sorted({b.n_dst for b in plan.boxes()}) == [3, 5]
+
+
 MID = Model(n_layers=2, hidden=512, n_heads=8, ffn=2048, vocab_true=4096, max_pos=64)
 TWELVE = Model(n_layers=2, hidden=192, n_heads=12, ffn=768, vocab_true=1536, max_pos=16)
 

@@ -140,7 +140,7 @@ def main() -> int:
     ap.add_argument("--ab", default=None, metavar="CFG;CFG;...",
                     help="compare settings inside ONE process on fixed buffers (differences between processes are larger than most "
                          "effects): each CFG is a comma list of key=value with keys streams, chunk, occupancy, variant (executor "
-                         "knobs), tile_bytes, max_multicast, share_reads (plan options) and dst_shift_kib (all buffers of a side in one "
+                         "knobs), tile_bytes, max_multicast, share_reads, pack_bytes (plan options) and dst_shift_kib (all buffers of a side in one "
                          "allocation, the destination side moved by that many KiB); prints one JSON line")
     ap.add_argument("--no-probe", action="store_true")
     ap.add_argument("--share-reads", action="store_true",
@@ -309,7 +309,7 @@ def main() -> int:
     return 0
 
 
-PLAN_KEYS = ("tile_bytes", "max_multicast", "share_reads")
+PLAN_KEYS = ("tile_bytes", "max_multicast", "share_reads", "pack_bytes")
 KNOB_DEFAULTS = {"streams": 4, "chunk": 0, "occupancy": 0, "variant": 0}
 
 

@@ -148,6 +148,12 @@ typedef struct {
                                  (then see tpx_segment.units); src_off / src_pitch / src_rank are unused,
                                  src_off = first row of the tile within the box (add src_off * segment pitch
                                  to the segment's offset) */
+#define TPX_TILE_PACK 5u      /* several short contiguous moves into the same destination buffer(s), done by one
+                                 workgroup so that none of them occupies a compute unit by itself: the tile is ONE
+                                 row of run_units 16-byte units, the concatenation of segments seg_first ..
+                                 seg_first + n_seg - 1; each segment has its own source (buffer, offset), its own
+                                 place in the destination buffer(s) (tpx_segment.dst_off) and its own length;
+                                 the tile's src_off, dst_off, pitches and src_rank are 0 and unused */
 typedef struct {
   uint64_t src_off, dst_off;  /* bytes, inside the rank buffers */
   uint64_t src_pitch, dst_pitch;
@@ -159,18 +165,19 @@ typedef struct {
   uint8_t  unit_log2;         /* 4 (16-byte vectors) when offsets, pitches and run length allow, else smaller */
   uint8_t  n_dst;             /* written to buffers dst_rank + k*dst_rank_stride, k < n_dst */
   uint8_t  dst_rank_stride;
-  uint32_t seg_first;         /* MERGE tiles: first segment, segments per row, units per segment */
+  uint32_t seg_first;         /* MERGE and PACK tiles: first segment, number of segments, units per segment (MERGE) */
   uint32_t n_seg;
   uint32_t seg_units;
   uint32_t pad_;
 } tpx_tile;
 
-/* One source of a MERGE tile: the rows of a source sub-tensor piece. */
+/* One source of a MERGE tile (the rows of a source sub-tensor piece) or one move of a PACK tile. */
 typedef struct {
-  uint64_t src_off;           /* byte offset of row 0 of the box in buffer src_rank */
-  uint64_t src_pitch;         /* bytes between rows */
+  uint64_t src_off;           /* MERGE: byte offset of row 0 of the box in buffer src_rank; PACK: of the move's first byte */
+  uint64_t src_pitch;         /* MERGE: bytes between rows; PACK: index of the segment's first unit within the tile */
   uint32_t src_rank;
-  uint32_t units;             /* width of the column block it contributes, in 16-byte units */
+  uint32_t units;             /* MERGE: width of the column block it contributes; PACK: length; in 16-byte units */
+  uint64_t dst_off;           /* PACK: byte offset of the move in the destination buffer(s); MERGE: 0 */
 } tpx_segment;
 
 typedef struct {
@@ -193,11 +200,16 @@ typedef struct {
  *   share_reads    0 (default): every destination rank reads from the holder section 6.5's locality rule picks for
  *                  it (its own device first), which minimises bytes_cross_rank; 1: all ranks of a replica group
  *                  read what the group's first rank reads, so a piece wanted by n replicas is read once and written
- *                  n times - fewer bytes through memory when all buffers share one GPU. */
+ *                  n times - fewer bytes through memory when all buffers share one GPU.
+ *   pack_bytes     contiguous, 16-byte aligned moves of at most this many bytes do not get a tile each: up to 64 of
+ *                  them that go to the same destination buffer(s) share one PACK tile.  0 = default (a quarter of
+ *                  the tile size in use); 1 = pack nothing; at most tile_bytes. */
 typedef struct {
   uint64_t tile_bytes;
   uint32_t max_multicast;
   uint32_t share_reads;
+  uint32_t pack_bytes;
+  uint32_t reserved_;         /* 0 */
 } tpx_plan_opts;
 
 /* Plan the transformation of the model state of `model` from configuration src to dst (section 4.2,

@@ -30,7 +30,7 @@ TPX_MAX_RANKS = 128
 SIDE_SRC, SIDE_DST = 0, 1
 MODEL_TIED_HEAD = 1
 BOX_COPY, BOX_FILL, BOX_TRANSPOSE = 0, 1, 2
-TILE_COPY, TILE_FILL, TILE_TRANSPOSE, TILE_GATHER, TILE_MERGE = 0, 1, 2, 3, 4
+TILE_COPY, TILE_FILL, TILE_TRANSPOSE, TILE_GATHER, TILE_MERGE, TILE_PACK = 0, 1, 2, 3, 4, 5
 
 
 class TpxError(RuntimeError):
@@ -77,7 +77,8 @@ class tpx_tile(C.Structure):
 
 
 class tpx_segment(C.Structure):
-    _fields_ = [("src_off", C.c_uint64), ("src_pitch", C.c_uint64), ("src_rank", C.c_uint32), ("units", C.c_uint32)]
+    _fields_ = [("src_off", C.c_uint64), ("src_pitch", C.c_uint64), ("src_rank", C.c_uint32), ("units", C.c_uint32),
+                ("dst_off", C.c_uint64)]
 
 
 class tpx_ptc(C.Structure):
@@ -87,7 +88,8 @@ class tpx_ptc(C.Structure):
 
 
 class tpx_plan_opts(C.Structure):
-    _fields_ = [("tile_bytes", C.c_uint64), ("max_multicast", C.c_uint32), ("share_reads", C.c_uint32)]
+    _fields_ = [("tile_bytes", C.c_uint64), ("max_multicast", C.c_uint32), ("share_reads", C.c_uint32),
+                ("pack_bytes", C.c_uint32), ("reserved_", C.c_uint32)]
 
 
 class tpx_query(C.Structure):
@@ -157,14 +159,14 @@ def _model_struct(n_layers, hidden, n_heads, ffn, vocab_true, max_pos=1024, voca
 
 
 def _opts_struct(opts) -> "C.POINTER(tpx_plan_opts)":
-    """opts: None or a dict with any of tile_bytes, max_multicast, share_reads."""
+    """opts: None or a dict with any of tile_bytes, max_multicast, share_reads, pack_bytes."""
     if not opts:
         return None
-    unknown = set(opts) - {"tile_bytes", "max_multicast", "share_reads"}
+    unknown = set(opts) - {"tile_bytes", "max_multicast", "share_reads", "pack_bytes"}
     if unknown:
         raise TpxError(TPX_ERR_INVALID_ARG, f"unknown plan option {sorted(unknown)[0]}")
     return C.pointer(tpx_plan_opts(int(opts.get("tile_bytes", 0)), int(opts.get("max_multicast", 0)),
-                                   int(opts.get("share_reads", 0))))
+                                   int(opts.get("share_reads", 0)), int(opts.get("pack_bytes", 0)), 0))
 
 
 def _parallel_struct(T, P, D, stage_first_layer=None, qkv_layout=0, w_transposed=0, rank_alive=None, shard_kinds=0,

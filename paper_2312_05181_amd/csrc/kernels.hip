@@ -193,6 +193,43 @@ __device__ __forceinline__ void merge_tile(const tpx_tile& t, const tpx_segment*
   else move_units<v4u, kThreads, U, NTL, NTS, false, false>(total, ds, src_of, dst_off);
 }
 
+// Pack tile: n_seg short contiguous moves into the same destination buffer(s), as one row of units.  Unit idx belongs to
+// the segment whose first unit is the largest one <= idx (found by bisection in LDS: entries past n_seg hold a
+// sentinel); source pointer and destination offset of every segment are staged in LDS like a merge tile's.
+template <int kThreads, int U, bool NTL, bool NTS>
+__device__ __forceinline__ void pack_tile(const tpx_tile& t, const tpx_segment* __restrict__ segs, const uint8_t* const* src_table,
+                                          const DstSet& ds, SegLds* lseg) {
+  uint32_t* lfirst = reinterpret_cast<uint32_t*>(lseg + kMaxSegLds);
+  for (uint32_t g = threadIdx.x; g < kMaxSegLds; g += kThreads) {
+    if (g < t.n_seg) {
+      const tpx_segment sg = segs[t.seg_first + g];
+      lseg[g].base = src_table[sg.src_rank] + sg.src_off;
+      lseg[g].pitch = sg.dst_off;
+      lfirst[g] = uint32_t(sg.src_pitch);  // first unit of the segment within the tile
+    } else {
+      lfirst[g] = 0xffffffffu;
+    }
+  }
+  __syncthreads();
+  auto seg_of = [&](uint32_t idx) -> uint32_t {
+    uint32_t g = 0;
+#pragma unroll
+    for (uint32_t step = kMaxSegLds / 2; step; step >>= 1)
+      if (lfirst[g + step] <= idx) g += step;
+    return g;
+  };
+  auto src_of = [&](uint32_t idx) -> const v4u* {
+    const uint32_t g = seg_of(idx);
+    return reinterpret_cast<const v4u*>(lseg[g].base + uint64_t(idx - lfirst[g]) * 16);
+  };
+  auto dst_off = [&](uint32_t idx) -> uint64_t {
+    const uint32_t g = seg_of(idx);
+    return lseg[g].pitch + uint64_t(idx - lfirst[g]) * 16;
+  };
+  if (ds.n > 1) move_units<v4u, kThreads, U, NTL, NTS, false, true>(t.run_units, ds, src_of, dst_off);
+  else move_units<v4u, kThreads, U, NTL, NTS, false, false>(t.run_units, ds, src_of, dst_off);
+}
+
 // Transposing tile: element (i, j) is contiguous in j on the source and in i on the destination.
 // Square sub-tiles of TS x TS elements (at least 256 bytes a side) go through LDS: 16-byte global loads
 // along j, element-wise LDS writes into the transposed position, 16-byte reads along i, 16-byte global
@@ -411,6 +448,10 @@ __global__ __launch_bounds__(kThreads) void tpx_execute_tiles(const tpx::Workspa
   }
   if (t.kind == TPX_TILE_MERGE) {
     merge_tile<kThreads, U, NTL, NTS>(t, segs, ptrs.src, ds, lseg);
+    return;
+  }
+  if (t.kind == TPX_TILE_PACK) {
+    pack_tile<kThreads, U, NTL, NTS>(t, segs, ptrs.src, ds, lseg);
     return;
   }
   const uint8_t* s = ptrs.src[t.src_rank] + t.src_off;

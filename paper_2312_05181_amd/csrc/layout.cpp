@@ -35,7 +35,7 @@ Tuning& tuning() {
 }
 
 tpx_status resolve_opts(const tpx_plan_opts* in, tpx_plan_opts& out) {
-  out = tpx_plan_opts{65536, 8, 0};
+  out = tpx_plan_opts{65536, 8, 0, 0, 0};
   if (!in) return TPX_OK;
   if (in->tile_bytes) {
     if (in->tile_bytes < 4096 || in->tile_bytes > 4194304 || (in->tile_bytes & (in->tile_bytes - 1)))
@@ -48,6 +48,9 @@ tpx_status resolve_opts(const tpx_plan_opts* in, tpx_plan_opts& out) {
   }
   if (in->share_reads > 1) return fail(TPX_ERR_INVALID_ARG, "share_reads must be 0 or 1");
   out.share_reads = in->share_reads;
+  if (in->reserved_) return fail(TPX_ERR_INVALID_ARG, "the reserved field of tpx_plan_opts must be 0");
+  if (in->pack_bytes > out.tile_bytes) return fail(TPX_ERR_INVALID_ARG, "pack_bytes must not exceed tile_bytes");
+  out.pack_bytes = in->pack_bytes;  // 0 = a quarter of the tile size in use, decided when the tiles are cut
   return TPX_OK;
 }
 

@@ -14,6 +14,7 @@
 // derives its equal-byte tiles from.
 #include <algorithm>
 #include <cstring>
+#include <map>
 
 #include "tpx_internal.hpp"
 
@@ -307,9 +308,28 @@ tpx_status tile_boxes(tpx_plan_s& plan, uint64_t tile_bytes) {
   plan.segments.clear();
   plan.uniform_tiles = true;
   for (const tpx_box& b : plan.boxes) plan.uniform_tiles = plan.uniform_tiles && b.n_dst == plan.boxes[0].n_dst;
+  // Short contiguous moves (biases, LayerNorm vectors, the replicated tensors of every layer) would each hold a compute
+  // unit for a full memory round trip while moving a few KiB: those that go to the same destination buffer(s) are
+  // set aside here and share PACK tiles, made after all other boxes.
+  const uint64_t pack_limit = plan.opts.pack_bytes ? plan.opts.pack_bytes : tile_bytes / 4;
+  std::vector<uint8_t> packed(plan.boxes.size(), 0);
+  std::map<uint64_t, std::vector<size_t>> pack_groups;  // (first destination, replicas, their stride) -> boxes, in plan order
   for (size_t bi = 0; bi < plan.boxes.size(); ++bi) {
     const tpx_box& b = plan.boxes[bi];
-    if (box_bytes(b) == 0) continue;
+    if (b.kind != TPX_BOX_COPY || b.ndim != 0 || !b.run_bytes || b.run_bytes > pack_limit || b.run_bytes > tile_bytes) continue;
+    if ((b.src_off | b.dst_off | b.run_bytes) % 16 || b.src_rank >= TPX_MAX_RANKS || b.dst_rank >= TPX_MAX_RANKS || b.n_dst > 255 ||
+        b.dst_rank_stride > 255)
+      continue;
+    pack_groups[uint64_t(b.dst_rank) | uint64_t(b.n_dst) << 32 | uint64_t(b.dst_rank_stride) << 48].push_back(bi);
+  }
+  for (auto it = pack_groups.begin(); it != pack_groups.end();) {
+    if (it->second.size() < 2) { it = pack_groups.erase(it); continue; }  // nothing to share a tile with
+    for (size_t bi : it->second) packed[bi] = 1;
+    ++it;
+  }
+  for (size_t bi = 0; bi < plan.boxes.size(); ++bi) {
+    const tpx_box& b = plan.boxes[bi];
+    if (box_bytes(b) == 0 || packed[bi]) continue;
     // merge(W) inside the tile: K consecutive moves that each bring one column block of the same
     // destination rows, together the whole row, become one MERGE box whose tiles write whole destination
     // rows and read K sources.  The blocks may differ in width (T 3 -> 4 cuts rows in thirds and quarters);
@@ -352,7 +372,7 @@ tpx_status tile_boxes(tpx_plan_s& plan, uint64_t tile_bytes) {
         f.seg_units = equal ? uint32_t(b.run_bytes / 16) : 0;
         for (uint64_t k = 0; k < K; ++k) {
           const tpx_box& c = plan.boxes[bi + k];
-          plan.segments.push_back(tpx_segment{c.src_off, c.src_stride[0], c.src_rank, uint32_t(c.run_bytes / 16)});
+          plan.segments.push_back(tpx_segment{c.src_off, c.src_stride[0], c.src_rank, uint32_t(c.run_bytes / 16), 0});
         }
         plan.flat.push_back(f);
         bi += K - 1;
@@ -460,6 +480,35 @@ tpx_status tile_boxes(tpx_plan_s& plan, uint64_t tile_bytes) {
       if (k < 0) break;
     }
   }
+  // PACK boxes: per destination, runs of at most kMaxSegLds moves and tile_bytes bytes, one tile each
+  for (const auto& group : pack_groups) {
+    size_t k = 0;
+    const std::vector<size_t>& ids = group.second;
+    while (k < ids.size()) {
+      const tpx_box& b0 = plan.boxes[ids[k]];
+      FlatBox f{};
+      f.kind = TPX_TILE_PACK;
+      f.unit_log2 = 4;
+      f.dst_rank = uint16_t(b0.dst_rank);
+      f.n_dst = uint8_t(b0.n_dst);
+      f.dst_rank_stride = uint8_t(b0.dst_rank_stride);
+      if (b0.dst_rank + uint64_t(b0.n_dst - 1) * b0.dst_rank_stride >= TPX_MAX_RANKS) return fail(TPX_ERR_INVALID_ARG, "rank out of range");
+      f.src_step = f.dst_step = 16;
+      f.nrows = f.rows_per_tile = 1;
+      f.chunks_per_row = 1;
+      f.seg_first = uint32_t(plan.segments.size());
+      uint64_t units = 0;
+      while (k < ids.size() && f.n_seg < kMaxSegLds && (units + plan.boxes[ids[k]].run_bytes / 16) * 16 <= tile_bytes) {
+        const tpx_box& c = plan.boxes[ids[k]];
+        plan.segments.push_back(tpx_segment{c.src_off, units, c.src_rank, uint32_t(c.run_bytes / 16), c.dst_off});
+        units += c.run_bytes / 16;
+        ++f.n_seg;
+        ++k;
+      }
+      f.run_units = f.chunk_units = uint32_t(units);
+      plan.flat.push_back(f);
+    }
+  }
   // prefix sums and coarse table
   uint64_t n_tiles = 0;
   plan.first_tile.resize(plan.flat.size() + 1);
@@ -495,7 +544,22 @@ tpx_status validate_tiles(tpx_plan_s& plan) {
         return fail(TPX_ERR_INVALID_ARG, "internal: a move writes outside its destination buffer");
       if (!plan.side[1].alive[r]) return fail(TPX_ERR_INVALID_ARG, "internal: a move targets a rank that is not to be built");
     }
-    if (t.kind == TPX_TILE_MERGE) {
+    if (t.kind == TPX_TILE_PACK) {
+      if (!t.n_seg || t.n_seg > kMaxSegLds || uint64_t(t.seg_first) + t.n_seg > plan.segments.size() || t.unit_log2 != 4 || t.nrows != 1)
+        return fail(TPX_ERR_INVALID_ARG, "internal: bad pack tile");
+      uint64_t first = 0;
+      for (uint32_t k = 0; k < t.n_seg; ++k) {
+        const tpx_segment& sg = plan.segments[t.seg_first + k];
+        if (!sg.units || sg.src_pitch != first) return fail(TPX_ERR_INVALID_ARG, "internal: bad pack segment");
+        first += sg.units;
+        if (sg.src_rank >= plan.side[0].bytes.size() || sg.src_off + uint64_t(sg.units) * 16 > plan.side[0].bytes[sg.src_rank])
+          return fail(TPX_ERR_INVALID_ARG, "internal: a packed move reads outside its source buffer");
+        for (uint32_t c = 0; c < t.n_dst; ++c)
+          if (sg.dst_off + uint64_t(sg.units) * 16 > plan.side[1].bytes[t.dst_rank + c * t.dst_rank_stride])
+            return fail(TPX_ERR_INVALID_ARG, "internal: a packed move writes outside its destination buffer");
+      }
+      if (first != t.run_units) return fail(TPX_ERR_INVALID_ARG, "internal: the moves of a pack tile do not make up its units");
+    } else if (t.kind == TPX_TILE_MERGE) {
       if (!t.n_seg || uint64_t(t.seg_first) + t.n_seg > plan.segments.size() || (!t.seg_units && t.n_seg > kMaxSegLds))
         return fail(TPX_ERR_INVALID_ARG, "internal: bad segment range");
       uint64_t row_units = 0;

@@ -116,7 +116,7 @@ struct tpx_plan_s {
   tpx::Side side[2];
   std::vector<tpx_box> boxes;
   std::vector<tpx::FlatBox> flat;     // what the GPU executes
-  std::vector<tpx_segment> segments;  // sources of MERGE boxes
+  std::vector<tpx_segment> segments;  // sources of MERGE boxes, moves of PACK boxes
   std::vector<uint32_t> first_tile;   // flat.size() + 1 prefix sums of tiles
   std::vector<uint32_t> coarse;       // box index of every 64th tile (+ sentinel)
   uint64_t n_tiles = 0;
@@ -124,7 +124,7 @@ struct tpx_plan_s {
   tpx_stats_t stats{};
   bool needs_lds = false;       // some tile is staged through LDS
   bool uniform_tiles = true;    // every tile has the same number of destinations (same cost per byte)
-  tpx_plan_opts opts{65536, 8, 0};  // the caller's options with defaults filled in
+  tpx_plan_opts opts{65536, 8, 0, 0, 0};  // the caller's options with defaults filled in
   uint64_t id = 0;              // process-unique, never 0: stamps the workspace header
   std::vector<uint8_t> image;   // host image of the whole workspace (header and tables), what an upload copies
 };

@@ -51,6 +51,22 @@ def run_tiles(plan, src_bufs, dst_bufs, cover=None):
                         np.add.at(cover[r], di, 1)
                     first += widths[g]
             continue
+        if t.kind == B.TILE_PACK:
+            # one row of units made of n_seg short moves, each with its own source and its own place in the destination
+            assert t.nrows == 1 and unit == 16 and 1 <= t.n_seg <= 64
+            first = 0
+            for g in range(t.n_seg):
+                sg = segs[t.seg_first + g]
+                assert sg.src_pitch == first and sg.units > 0
+                n = sg.units * 16
+                for c in range(t.n_dst):
+                    r = t.dst_rank + c * t.dst_rank_stride
+                    dst_bufs[r][sg.dst_off:sg.dst_off + n] = src_bufs[sg.src_rank][sg.src_off:sg.src_off + n]
+                    if cover is not None:
+                        cover[r][sg.dst_off:sg.dst_off + n] += 1
+                first += sg.units
+            assert first == t.run_units
+            continue
         i = np.arange(t.nrows, dtype=np.int64)[:, None, None]
         j = np.arange(t.run_units, dtype=np.int64)[None, :, None]
         k = np.arange(unit, dtype=np.int64)[None, None, :]

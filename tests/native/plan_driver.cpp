@@ -31,7 +31,18 @@ static void walk(tpx_plan_t* p, uint64_t stride) {
     CHECK(t.nrows && t.run_units && t.n_dst);
     const uint64_t dlast = t.dst_off + (t.nrows - 1ull) * t.dst_pitch + (t.run_units - 1ull) * t.dst_step + unit;
     for (uint32_t c = 0; c < t.n_dst; ++c) CHECK(dlast <= tpx_buffer_bytes(p, TPX_SIDE_DST, t.dst_rank + c * t.dst_rank_stride));
-    if (t.kind == TPX_TILE_MERGE) {
+    if (t.kind == TPX_TILE_PACK) {
+      uint64_t first = 0;
+      for (uint32_t g = 0; g < t.n_seg; ++g) {
+        tpx_segment sg;
+        CHECK(tpx_get_segment(p, t.seg_first + g, &sg) == TPX_OK);
+        CHECK(sg.src_pitch == first && sg.units);
+        first += sg.units;
+        CHECK(sg.src_off + sg.units * 16ull <= tpx_buffer_bytes(p, TPX_SIDE_SRC, sg.src_rank));
+        for (uint32_t c = 0; c < t.n_dst; ++c) CHECK(sg.dst_off + sg.units * 16ull <= tpx_buffer_bytes(p, TPX_SIDE_DST, t.dst_rank + c * t.dst_rank_stride));
+      }
+      CHECK(first == t.run_units);
+    } else if (t.kind == TPX_TILE_MERGE) {
       for (uint32_t g = 0; g < t.n_seg; ++g) {
         tpx_segment sg;
         CHECK(tpx_get_segment(p, t.seg_first + g, &sg) == TPX_OK);

@@ -579,6 +579,25 @@ def test_multicast_to_the_largest_replica_count(cuda):
     assert sorted({b.n_dst for b in plan.boxes()}) == [3, 5]
 
 
+DEEP = Model(n_layers=24, hidden=64, n_heads=4, ffn=256, vocab_true=512, max_pos=32)
+
+
+@pytest.mark.parametrize("opts", [None, dict(pack_bytes=1), dict(pack_bytes=512), dict(tile_bytes=4096, pack_bytes=4096),
+                                  dict(tile_bytes=65536, pack_bytes=65536)])
+def test_short_moves_packed_into_shared_tiles(cuda, opts):
+    """Biases and LayerNorm vectors share PACK tiles (up to 64 moves per tile, each with its own source and destination
+    offset): single and replicated destinations, more moves per destination than one tile takes, every pack limit from
+    none to the whole tile."""
+    plan = _check_small(WIDE, synth.MIX_GPT, Parallel(4, 1, 1), Parallel(2, 2, 3), opts=opts)
+    packs = [t for t in plan.tiles() if t.kind == tpx.binding.TILE_PACK]
+    assert bool(packs) == (opts != dict(pack_bytes=1)) and {t.n_dst for t in packs} <= {1, 3}
+    plan = _check_small(DEEP, synth.MIX_GPT, Parallel(2, 1, 1), Parallel(4, 1, 2), opts=opts)
+    packs = [t for t in plan.tiles() if t.kind == tpx.binding.TILE_PACK]
+    if opts != dict(pack_bytes=1):
+        assert len(packs) > 8 and {t.n_dst for t in packs} == {2} and (opts is not None or max(t.n_seg for t in packs) == 64)
+    _check_small(ODD, ODD_MIX, Parallel(3, 1, 2), Parallel(4, 1, 1, w_transposed=1), opts=opts)
+
+
 MID = Model(n_layers=2, hidden=512, n_heads=8, ffn=2048, vocab_true=4096, max_pos=64)
 TWELVE = Model(n_layers=2, hidden=192, n_heads=12, ffn=768, vocab_true=1536, max_pos=16)
 

@@ -412,7 +412,8 @@ def test_error_codes():
     assert st(lambda: tpx.tpx_set_option("chunk", 5000)) == B.TPX_ERR_INVALID_ARG
     assert st(lambda: tpx.tpx_set_option("occupancy", 17)) == B.TPX_ERR_INVALID_ARG
     one = dict(T=1, P=1, D=1)
-    for bad_opts in (dict(tile_bytes=5000), dict(tile_bytes=2048), dict(max_multicast=129), dict(share_reads=2), dict(tiles=1)):
+    for bad_opts in (dict(tile_bytes=5000), dict(tile_bytes=2048), dict(max_multicast=129), dict(share_reads=2), dict(tiles=1),
+                     dict(pack_bytes=65537), dict(tile_bytes=4096, pack_bytes=8192)):
         assert st(lambda: tpx.tpx_plan(m, one, one, bad_opts)) == B.TPX_ERR_INVALID_ARG
     # lists whose length the library cannot check are checked by the binding
     assert st(lambda: tpx.tpx_plan(m, dict(T=1, P=2, D=1, stage_first_layer=(0, 2)), one)) == B.TPX_ERR_INVALID_ARG
@@ -437,10 +438,53 @@ def test_tiles_are_bounded_and_vector_aligned_on_the_headline_workload():
     for i in range(0, plan.num_tiles(), 997):
         t = B.tpx_tile()
         B._check(B._lib.tpx_get_tile(plan._h, i, t))
-        assert t.unit_log2 == 4 and t.kind in (B.TILE_COPY, B.TILE_MERGE)
+        assert t.unit_log2 == 4 and t.kind in (B.TILE_COPY, B.TILE_MERGE, B.TILE_PACK)
         assert t.nrows * t.run_units * 16 <= 131072
         total += 1
     assert total > 300
+
+
+def pack_tiles(plan):
+    """The PACK tiles of a plan: they are its last tiles."""
+    out = []
+    for i in range(plan.num_tiles() - 1, -1, -1):
+        t = B.tpx_tile()
+        B._check(B._lib.tpx_get_tile(plan._h, i, t))
+        if t.kind != B.TILE_PACK:
+            break
+        out.append(t)
+    return out[::-1]
+
+
+def test_short_moves_share_pack_tiles():
+    """BERT-large shape, T 4 -> 8: biases and LayerNorm vectors (a few KiB each) are a few percent of the tiles when every one
+    has its own; packed, up to 64 of them that go to the same destination buffer share a tile.  Everything else about the plan
+    stays as it is, and the packed plan interpreted on the CPU still writes every destination byte exactly once."""
+    import bench
+    mk_, s_, d_, _, _ = bench.WORKLOADS["bert-large_(4,1,1)->(8,1,1)"]
+    apart = tpx.tpx_plan(mk_, s_, d_, dict(pack_bytes=1))
+    packed = tpx.tpx_plan(mk_, s_, d_)
+    a, p = apart.stats(), packed.stats()
+    assert not pack_tiles(apart) and len(apart.segments()) == 0
+    assert {k: a[k] for k in a if k not in ("n_tiles", "plan_ns")} == {k: p[k] for k in p if k not in ("n_tiles", "plan_ns")}
+    packs = pack_tiles(packed)
+    segs = packed.segments()
+    moved = sum(t.n_seg for t in packs)
+    assert a["n_tiles"] - p["n_tiles"] == moved - len(packs) and moved > 2000 and len(packs) <= moved // 8
+    assert {t.dst_rank for t in packs} == set(range(8)) and all(t.run_units * 16 <= 65536 and t.n_seg <= 64 for t in packs)
+    assert all(segs[t.seg_first + g].units * 16 <= 16384 for t in packs for g in range(t.n_seg))
+    # a small model through the CPU interpreter: packed and unpacked plans write the same bytes, each exactly once
+    for opts in (None, dict(pack_bytes=1), dict(pack_bytes=512), dict(tile_bytes=4096, pack_bytes=4096)):
+        src, dst = Parallel(4, 1, 1), Parallel(2, 2, 3)
+        plan = plan_for(WIDE, src, dst, opts=opts)
+        assert bool(pack_tiles(plan)) == (opts != dict(pack_bytes=1))
+        src_bufs = H.np_bufs(H.make_src_bufs(WIDE, src, 7, H.synth.MIX_GPT))
+        want = oreshard.reshard(WIDE, src, dst, src_bufs)
+        got = [np.full(plan.buffer_bytes(1, r), H.POISON, dtype=np.uint8) for r in range(plan.num_buffers(1))]
+        cover = [np.zeros(len(g), dtype=np.int32) for g in got]
+        host_exec.run_tiles(plan, src_bufs, got, cover)
+        assert all(np.array_equal(g, w) for g, w in zip(got, want))
+        assert all(c.max() <= 1 for c in cover)
 
 
 def test_row_parallel_merges_become_merge_tiles():
@@ -449,8 +493,9 @@ def test_row_parallel_merges_become_merge_tiles():
     model, src, dst, _, _ = H.CONFIGS[4]
     plan = plan_for(model, src, dst)
     segs = plan.segments()
-    assert len(segs) == model.n_layers * len(model.state_elem_bytes) * 2 * 8
-    assert sorted({g.src_rank for g in segs}) == list(range(8))
+    n_packed = sum(t.n_seg for t in pack_tiles(plan))
+    assert len(segs) - n_packed == model.n_layers * len(model.state_elem_bytes) * 2 * 8      # the segments of the merges come first
+    assert sorted({g.src_rank for g in segs[:len(segs) - n_packed]}) == list(range(8))
     merge_bytes = 0
     for i in range(0, plan.num_tiles(), 101):
         t = B.tpx_tile()
@@ -464,7 +509,8 @@ def test_row_parallel_merges_become_merge_tiles():
     model5, src5, dst5, _, _ = H.CONFIGS[5]
     plan5 = plan_for(model5, src5, dst5)
     segs5 = plan5.segments()
-    assert len(segs5) == model5.n_layers * len(model5.state_elem_bytes) * 2 * 2 * 2     # 2 weights x 2 middle quarters x 2 pieces
+    n_packed5 = sum(t.n_seg for t in pack_tiles(plan5))
+    assert len(segs5) - n_packed5 == model5.n_layers * len(model5.state_elem_bytes) * 2 * 2 * 2     # 2 weights x 2 middle quarters x 2 pieces
     irregular = 0
     for i in range(0, plan5.num_tiles(), 53):
         t = B.tpx_tile()

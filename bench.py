@@ -254,7 +254,7 @@ def main() -> int:
                 "kernel_ms_min": round(min(kernel_ms), 4), "kernel_ms_median": round(sorted(kernel_ms)[len(kernel_ms) // 2], 4),
                 "algorithmic_bytes_per_launch": state_bytes}
 
-    probe = memcpy_probe = probe_bytes = None
+    probe = memcpy_probe = probe_bytes = read_probe = write_probe = None
     if not args.no_probe:
         n = min(8 << 30, min(b.numel() for b in src_bufs if b.numel()) // 16 * 16, dst_bufs[0].numel() // 16 * 16)
         a, b = src_bufs[0], dst_bufs[0]
@@ -277,6 +277,26 @@ def main() -> int:
         e1.record()
         torch.cuda.synchronize()
         memcpy_probe = round(2 * n * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+        # pure read and pure write streams (the library's yardsticks): a copy lies between the two
+        sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
+        for which in ("read", "fill"):
+            def one():
+                if which == "read":
+                    tpx.tpx_probe_read(a.data_ptr(), n, sink.data_ptr(), stream)
+                else:
+                    tpx.tpx_probe_fill(b.data_ptr(), n, 0x5A5A5A5A, stream)
+            for _ in range(2):
+                one()
+            e0.record()
+            for _ in range(5):
+                one()
+            e1.record()
+            torch.cuda.synchronize()
+            rate = round(n * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+            if which == "read":
+                read_probe = rate
+            else:
+                write_probe = rate
 
     cpu = None
     if args.cpu_layers > 0:
@@ -301,6 +321,10 @@ def main() -> int:
         "copy_probe_GBps": probe,
         "copy_probe_bytes": probe_bytes,
         "memcpy_d2d_GBps": memcpy_probe,
+        "read_probe_GBps": read_probe,
+        "write_probe_GBps": write_probe,
+        # the rate of a memory that serves the reads at the read-only rate and the writes at the write-only rate, in turn
+        "read_write_mix_GBps": round(2 / (1 / read_probe + 1 / write_probe), 1) if read_probe and write_probe else None,
         "setup_s": round(setup_s, 1),
         "roofline": roofline,
         "cpu_baseline": cpu,

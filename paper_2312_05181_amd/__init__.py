@@ -5,7 +5,7 @@ The binding (and with it libtpx.so) is loaded on first use of any name below, so
 no fallback: without the library that first use raises ImportError."""
 
 __all__ = ["EXPORTS", "LIB_PATH", "Plan", "TpxError", "tpx_execute", "tpx_execute_static", "tpx_free", "tpx_param_name", "tpx_plan",
-           "tpx_plan_dataset", "tpx_plan_ptc", "tpx_plan_query", "tpx_probe_copy", "tpx_set_option", "tpx_workspace_forget"]
+           "tpx_plan_dataset", "tpx_plan_ptc", "tpx_plan_query", "tpx_probe_copy", "tpx_probe_fill", "tpx_probe_read", "tpx_set_option", "tpx_workspace_forget"]
 
 
 def __getattr__(name):

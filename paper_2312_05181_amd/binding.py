@@ -136,6 +136,8 @@ _sigs = {
     "tpx_last_error": (C.c_char_p, []),
     "tpx_set_option": (C.c_int, [C.c_char_p, C.c_uint64]),
     "tpx_probe_copy": (C.c_int, [_P, _P, C.c_uint64, _P]),
+    "tpx_probe_read": (C.c_int, [_P, C.c_uint64, _P, _P]),
+    "tpx_probe_fill": (C.c_int, [_P, C.c_uint64, C.c_uint32, _P]),
 }
 for _name, (_res, _args) in _sigs.items():
     _f = getattr(_lib, _name)
@@ -409,6 +411,14 @@ def tpx_set_option(key: str, value: int) -> None:
 
 def tpx_probe_copy(dst_ptr: int, src_ptr: int, nbytes: int, stream: int = 0) -> None:
     _check(_lib.tpx_probe_copy(_P(dst_ptr), _P(src_ptr), nbytes, _P(stream)))
+
+
+def tpx_probe_read(src_ptr: int, nbytes: int, sink_ptr: int, stream: int = 0) -> None:
+    _check(_lib.tpx_probe_read(_P(src_ptr), nbytes, _P(sink_ptr), _P(stream)))
+
+
+def tpx_probe_fill(dst_ptr: int, nbytes: int, value: int, stream: int = 0) -> None:
+    _check(_lib.tpx_probe_fill(_P(dst_ptr), nbytes, value, _P(stream)))
 
 
 def tpx_param_name(name: int) -> Optional[str]:

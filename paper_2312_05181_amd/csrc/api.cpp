@@ -368,6 +368,21 @@ tpx_status tpx_set_option(const char* key, uint64_t value) {
   return fail(TPX_ERR_INVALID_ARG, std::string("unknown option ") + key);
 }
 
+tpx_status tpx_probe_read(const void* src, uint64_t nbytes, void* sink, void* hip_stream) {
+  if (!src || !sink) return fail(TPX_ERR_INVALID_ARG, "tpx_probe_read: NULL argument");
+  if (nbytes % 16) return fail(TPX_ERR_INVALID_ARG, "tpx_probe_read: size must be a multiple of 16");
+  if (reinterpret_cast<uintptr_t>(src) % 16 || reinterpret_cast<uintptr_t>(sink) % 16)
+    return fail(TPX_ERR_MISALIGNED, "tpx_probe_read: pointers must be 16-byte aligned");
+  return hip_probe_read(src, nbytes, sink, hip_stream);
+}
+
+tpx_status tpx_probe_fill(void* dst, uint64_t nbytes, uint32_t value, void* hip_stream) {
+  if (!dst) return fail(TPX_ERR_INVALID_ARG, "tpx_probe_fill: NULL argument");
+  if (nbytes % 16) return fail(TPX_ERR_INVALID_ARG, "tpx_probe_fill: size must be a multiple of 16");
+  if (reinterpret_cast<uintptr_t>(dst) % 16) return fail(TPX_ERR_MISALIGNED, "tpx_probe_fill: the pointer must be 16-byte aligned");
+  return hip_probe_fill(dst, nbytes, value, hip_stream);
+}
+
 tpx_status tpx_probe_copy(void* dst, const void* src, uint64_t nbytes, void* hip_stream) {
   if (!dst || !src) return fail(TPX_ERR_INVALID_ARG, "tpx_probe_copy: NULL argument");
   if (nbytes % 16) return fail(TPX_ERR_INVALID_ARG, "tpx_probe_copy: size must be a multiple of 16");

@@ -159,6 +159,8 @@ tpx_status hip_upload_tables(void* workspace, const tpx_plan_s& plan, void* stre
 tpx_status hip_launch_tiles(const void* workspace, const tpx_plan_s& plan, const void* const* src, uint32_t n_src,
                             void* const* dst, uint32_t n_dst, uint64_t variant, void* stream);
 tpx_status hip_probe_copy(void* dst, const void* src, uint64_t nbytes, void* stream);
+tpx_status hip_probe_read(const void* src, uint64_t nbytes, void* sink, void* stream);
+tpx_status hip_probe_fill(void* dst, uint64_t nbytes, uint32_t value, void* stream);
 tpx_status hip_read_header(const void* workspace, void* stream, WorkspaceHeader* out);
 // Like hip_upload_tables + hip_launch_tiles with the tables in the library's own static device array of
 // TPX_STATIC_WORKSPACE_BYTES (one per GPU); allocates nothing.

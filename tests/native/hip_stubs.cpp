@@ -8,6 +8,8 @@ tpx_status hip_launch_tiles(const void*, const tpx_plan_s&, const void* const*, 
   return fail(TPX_ERR_HIP, "stub: no GPU in this build");
 }
 tpx_status hip_probe_copy(void*, const void*, uint64_t, void*) { return fail(TPX_ERR_HIP, "stub: no GPU in this build"); }
+tpx_status hip_probe_read(const void*, uint64_t, void*, void*) { return fail(TPX_ERR_HIP, "stub: no GPU in this build"); }
+tpx_status hip_probe_fill(void*, uint64_t, uint32_t, void*) { return fail(TPX_ERR_HIP, "stub: no GPU in this build"); }
 tpx_status hip_execute_static(const tpx_plan_s&, const void* const*, uint32_t, void* const*, uint32_t, uint64_t, void*) {
   return fail(TPX_ERR_HIP, "stub: no GPU in this build");
 }

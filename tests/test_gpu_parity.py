@@ -275,6 +275,27 @@ def test_probe_copy(cuda):
 # ---------------------------------------------------------------------------------------------
 # the full-size workloads, in the launch configuration the benchmark times
 # ---------------------------------------------------------------------------------------------
+def test_read_and_fill_probes(cuda):
+    """The write-only yardstick writes exactly the bytes it is given, the read-only one touches nothing but (at most) its
+    16-byte sink; both refuse what they cannot take."""
+    n = (1 << 20) + 48                                   # a ragged last workgroup
+    buf = G.alloc(n + 64, 0x11)
+    stream = torch.cuda.current_stream().cuda_stream
+    tpx.tpx_probe_fill(buf.data_ptr() + 16, n, 0xC3C3C3C3, stream)
+    torch.cuda.synchronize()
+    host = buf.cpu().numpy()
+    assert (host[:16] == 0x11).all() and (host[16:16 + n] == 0xC3).all() and (host[16 + n:] == 0x11).all()
+    sink = G.alloc(16, 0)
+    tpx.tpx_probe_read(buf.data_ptr() + 16, n, sink.data_ptr(), stream)
+    torch.cuda.synchronize()
+    assert np.array_equal(buf.cpu().numpy(), host)
+    tpx.tpx_probe_read(buf.data_ptr(), 0, sink.data_ptr(), stream)
+    for bad in (lambda: tpx.tpx_probe_fill(buf.data_ptr() + 8, 64, 0, stream), lambda: tpx.tpx_probe_read(buf.data_ptr(), 24, sink.data_ptr(), stream),
+                lambda: tpx.tpx_probe_read(buf.data_ptr(), 64, 0, stream), lambda: tpx.tpx_probe_fill(0, 64, 0, stream)):
+        with pytest.raises(tpx.TpxError):
+            bad()
+
+
 def _sample_ids(model):
     L = model.n_layers
     ids = [0, 1, 2, 3]

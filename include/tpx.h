@@ -392,9 +392,9 @@ tpx_status tpx_set_option(const char* key, uint64_t value);
  * calibration point for hardware traffic counters.  Errors: INVALID_ARG, MISALIGNED, HIP. */
 tpx_status tpx_probe_copy(void* dst, const void* src, uint64_t nbytes, void* hip_stream);
 
-/* Read-only and write-only yardsticks: what the memory gives a pure read stream and a pure write stream (512-thread
- * workgroups, eight nontemporal 16-byte accesses per thread; reads as 4 parts of the range side by side, writes as 8
- * with one workgroup per compute unit: the best launch found for either); a copy has to retire both kinds.
+/* Read-only and write-only yardsticks: what the memory gives a pure read stream and a pure write stream in the
+ * launch shape and tile order of tpx_execute's default copy tile (which is within 1 % of the best write-only and
+ * within 3 % of the best read-only launch found); a copy has to retire both kinds.
  * tpx_probe_read reads nbytes (multiple of 16) from DEVICE src; `sink` is 16 DEVICE bytes the kernel may write
  * (it does so only when the words a thread read XOR to one particular value: that dependency is what keeps the
  * reads from being optimised away).  tpx_probe_fill writes the 32-bit `value` over nbytes of DEVICE dst.

@@ -491,33 +491,48 @@ __global__ __launch_bounds__(kThreads) void tpx_execute_tiles(const tpx::Workspa
   }
 }
 
-// Read-only and write-only yardsticks: what this memory gives a pure read and a pure write stream.  512-thread
-// workgroups, eight nontemporal 16-byte accesses per thread, all issued at once (64 KiB per workgroup, the copy tile's
-// shape), `fronts` parts of the range advancing side by side like the tile kernel's streams.  The best launch found
-// for either, among 256/512/1024 threads x 4/8/16 accesses x 1/4/8 fronts with and without an occupancy cap: reads
-// with 4 fronts and no cap (7.0-7.2 TB/s; every shape is within 4 % of that), writes with 8 fronts and one workgroup
-// per CU (6.7 TB/s; other shapes 5.4-6.6).
+// Read-only and write-only yardsticks: what this memory gives a pure read and a pure write stream in the launch shape
+// and tile order of the default copy tile (512 threads x 8 nontemporal 16-byte accesses all issued at once, one
+// workgroup per CU, 4 streams, every XCD taking runs of 8 consecutive 64 KiB chunks).  Among 256/512/1024 threads x
+// 4/8/16 accesses x 1...256 fronts, with and without the occupancy cap and the per-XCD runs, that shape is within 1 %
+// of the best write-only rate found (6.7-6.8 TB/s; without per-XCD runs 5.5-6.1, with more than one workgroup per CU
+// 5.2-6.6) and within 3 % of the best read-only rate (7.0-7.2 TB/s in every shape).
 constexpr int kOneShotThreads = 512;
 constexpr uint64_t kOneShotUnits = uint64_t(kOneShotThreads) * 8;
-constexpr uint32_t kReadFronts = 4, kFillFronts = 8;
-constexpr uint32_t kFillLds = ((kLdsPerCu / 2) & ~255u) + 256;  // one workgroup fits a CU, two do not
-__device__ __forceinline__ uint64_t one_shot_base(uint32_t fronts) {  // the grid is a multiple of fronts
-  const uint32_t per_front = gridDim.x / fronts;
-  return (uint64_t(blockIdx.x % fronts) * per_front + blockIdx.x / fronts) * kOneShotUnits + threadIdx.x;
+constexpr uint32_t kOneShotStreams = 4, kOneShotRun = 8;
+constexpr uint32_t kOneShotLds = ((kLdsPerCu / 2) & ~255u) + 256;  // one workgroup fits a CU, two do not
+// First unit of this workgroup's chunk, or ~0 if the workgroup is one of those the grid was rounded up by.
+__device__ __forceinline__ uint64_t one_shot_base(uint64_t n_chunks) {
+  const uint32_t x = blockIdx.x & 7, i = blockIdx.x >> 3, per = 8 / kOneShotStreams, stream = x % kOneShotStreams, member = x / kOneShotStreams;
+  const uint64_t q = (n_chunks + kOneShotStreams - 1) / kOneShotStreams;
+  const uint64_t j = (uint64_t(i / kOneShotRun) * per + member) * kOneShotRun + i % kOneShotRun;
+  if (j >= q) return ~0ull;
+  return (stream * q + j) * kOneShotUnits + threadIdx.x;  // chunks past the end are caught by the callers' idx < n
 }
-__global__ __launch_bounds__(kOneShotThreads) void tpx_probe_read_kernel(const v4u* __restrict__ s, uint64_t n, v4u* __restrict__ sink) {
-  const uint64_t base = one_shot_base(kReadFronts);
+__global__ __launch_bounds__(kOneShotThreads) void tpx_probe_read_kernel(const v4u* __restrict__ s, uint64_t n, uint64_t n_chunks,
+                                                                         v4u* __restrict__ sink) {
+  const uint64_t base = one_shot_base(n_chunks);
+  if (base == ~0ull) return;
   v4u acc = zero_of<v4u>();
+  if (base - threadIdx.x + kOneShotUnits <= n) {  // a whole chunk: all eight loads in flight before the first use
+    v4u r[8];
 #pragma unroll
-  for (int k = 0; k < 8; ++k) {
-    const uint64_t idx = base + uint64_t(k) * kOneShotThreads;
-    if (idx < n) acc ^= __builtin_nontemporal_load(s + idx);
+    for (int k = 0; k < 8; ++k) r[k] = __builtin_nontemporal_load(s + base + uint64_t(k) * kOneShotThreads);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc ^= r[k];
+  } else {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const uint64_t idx = base + uint64_t(k) * kOneShotThreads;
+      if (idx < n) acc ^= __builtin_nontemporal_load(s + idx);
+    }
   }
   // keeps the loads alive; for data that is not adversarial the store happens about once in 2^32 threads
   if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) *sink = acc;
 }
-__global__ __launch_bounds__(kOneShotThreads) void tpx_probe_fill_kernel(v4u* __restrict__ d, uint64_t n, uint32_t value) {
-  const uint64_t base = one_shot_base(kFillFronts);
+__global__ __launch_bounds__(kOneShotThreads) void tpx_probe_fill_kernel(v4u* __restrict__ d, uint64_t n, uint64_t n_chunks, uint32_t value) {
+  const uint64_t base = one_shot_base(n_chunks);
+  if (base == ~0ull) return;
   const v4u v = {value, value, value, value};
 #pragma unroll
   for (int k = 0; k < 8; ++k) {
@@ -713,16 +728,27 @@ tpx_status hip_read_header(const void* workspace, void* stream, WorkspaceHeader*
   return TPX_OK;
 }
 
+namespace {
+// Grid of the one-shot probes for n units: per stream ceil(chunks / streams) slots, rounded up to whole runs of all
+// the XCDs of the stream (see one_shot_base).  0 = too large for one launch.
+uint32_t one_shot_grid(uint64_t n, uint64_t& n_chunks) {
+  n_chunks = (n + kOneShotUnits - 1) / kOneShotUnits;
+  const uint64_t q = (n_chunks + kOneShotStreams - 1) / kOneShotStreams, unit = uint64_t(8 / kOneShotStreams) * kOneShotRun;
+  const uint64_t grid = (q + unit - 1) / unit * unit * kOneShotStreams;
+  return grid > 0x7fffffffull ? 0 : uint32_t(grid);
+}
+}  // namespace
+
 tpx_status hip_probe_read(const void* src, uint64_t nbytes, void* sink, void* stream) {
   if (nbytes == 0) return TPX_OK;
   const v4u* a_src = static_cast<const v4u*>(src);
-  uint64_t a_n = nbytes / 16;
+  uint64_t a_n = nbytes / 16, a_chunks = 0;
   v4u* a_sink = static_cast<v4u*>(sink);
-  void* args[] = {&a_src, &a_n, &a_sink};
-  const uint64_t grid = ((a_n + kOneShotUnits - 1) / kOneShotUnits + kReadFronts - 1) / kReadFronts * kReadFronts;
-  if (grid > 0x7fffffffull) return fail(TPX_ERR_INVALID_ARG, "tpx_probe_read: too many bytes for one launch");
-  const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(tpx_probe_read_kernel), dim3(uint32_t(grid)), dim3(kOneShotThreads),
-                                       args, 0, static_cast<hipStream_t>(stream));
+  const uint32_t grid = one_shot_grid(a_n, a_chunks);
+  if (!grid) return fail(TPX_ERR_INVALID_ARG, "tpx_probe_read: too many bytes for one launch");
+  void* args[] = {&a_src, &a_n, &a_chunks, &a_sink};
+  const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(tpx_probe_read_kernel), dim3(grid), dim3(kOneShotThreads), args,
+                                       kOneShotLds, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return hip_fail(e, "launching the read probe");
   return TPX_OK;
 }
@@ -730,13 +756,13 @@ tpx_status hip_probe_read(const void* src, uint64_t nbytes, void* sink, void* st
 tpx_status hip_probe_fill(void* dst, uint64_t nbytes, uint32_t value, void* stream) {
   if (nbytes == 0) return TPX_OK;
   v4u* a_dst = static_cast<v4u*>(dst);
-  uint64_t a_n = nbytes / 16;
+  uint64_t a_n = nbytes / 16, a_chunks = 0;
   uint32_t a_value = value;
-  void* args[] = {&a_dst, &a_n, &a_value};
-  const uint64_t grid = ((a_n + kOneShotUnits - 1) / kOneShotUnits + kFillFronts - 1) / kFillFronts * kFillFronts;
-  if (grid > 0x7fffffffull) return fail(TPX_ERR_INVALID_ARG, "tpx_probe_fill: too many bytes for one launch");
-  const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(tpx_probe_fill_kernel), dim3(uint32_t(grid)), dim3(kOneShotThreads),
-                                       args, kFillLds, static_cast<hipStream_t>(stream));
+  const uint32_t grid = one_shot_grid(a_n, a_chunks);
+  if (!grid) return fail(TPX_ERR_INVALID_ARG, "tpx_probe_fill: too many bytes for one launch");
+  void* args[] = {&a_dst, &a_n, &a_chunks, &a_value};
+  const hipError_t e = hipLaunchKernel(reinterpret_cast<const void*>(tpx_probe_fill_kernel), dim3(grid), dim3(kOneShotThreads), args,
+                                       kOneShotLds, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return hip_fail(e, "launching the fill probe");
   return TPX_OK;
 }

@@ -364,6 +364,35 @@ def test_generic_collections_at_scale_gpu(cuda, name):
         assert torch.equal(have, exact[r]), r
 
 
+@pytest.mark.gpu
+@pytest.mark.parametrize("eb", [1, 2, 4, 8])
+def test_transposing_blocks_of_every_element_size_gpu(cuda, eb):
+    """A [1100, 1048] tensor stored row-major in two row halves and wanted column-major in three column thirds, the last third
+    twice (replicas: one multicast move): 2-, 4- and 8-byte elements go through the one-shot 64 KiB transposing blocks where a
+    block is full and aligned and through the general path at the ragged edges, 1-byte elements through the general path only."""
+    from tests import gpu_util as G
+    shape = (1100, 1048)
+    src = pack([[(0, 0, eb, shape, (a, 0), (b, shape[1]), (0, 1))] for a, b in ((0, 512), (512, 1100))])
+    cols = ((0, 352), (352, 704), (704, 1048), (704, 1048))
+    dst = pack([[(0, 0, eb, shape, (0, c), (shape[0], d), (1, 0))] for c, d in cols])
+    mix = ((eb, "index"),)
+    a = []
+    for entries, n in src:
+        b = torch.full((n,), H.SRC_GAP, dtype=torch.uint8)
+        synth.fill_buffer(b, [H.desc_of(e) for e in entries], 29, mix)
+        a.append(b)
+    want = oreshard.reshard_ptc(src, dst, H.np_bufs(a))
+    plan = plan_of(src, dst)
+    tiles = plan.tiles()
+    assert {t.kind for t in tiles} == {B.TILE_TRANSPOSE} and any(t.n_dst == 2 for t in tiles)
+    full = [t for t in tiles if t.nrows * t.run_units * eb == 65536]
+    assert bool(full) == (eb > 1)
+    got, _ = G.execute(plan, [x.cuda() for x in a])
+    torch.cuda.synchronize()
+    for r in range(len(dst)):
+        assert np.array_equal(got[r].cpu().numpy(), want[r]), r
+
+
 def _long_run_pair(n, eb, kind):
     """One rank on either side; a small tensor changes place with a long one, so the long one moves as a single contiguous run
     between different offsets."""

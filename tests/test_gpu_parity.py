@@ -646,8 +646,8 @@ def test_merges_of_unequal_column_blocks(cuda, src, dst):
     (Parallel(1, 1, 1), Parallel(8, 1, 1, w_transposed=1, qkv_layout=1)),
 ])
 def test_transposed_storage_mid_size(cuda, src, dst):
-    """[in, out] weight storage on one side: full 128 x 128 (bf16) and 64 x 64 (fp32) sub-tiles take the
-    vectorised LDS path, edges the element path; compared byte for byte with the oracle."""
+    """[in, out] weight storage on one side: full 64 KiB blocks (512 x 64 bf16, 256 x 64 fp32) are transposed in one shot
+    through LDS, edges take the general path; compared byte for byte with the oracle."""
     print("case", src, dst, flush=True)
     plan = _check_small(MID, synth.MIX_GPT, src, dst, seed=23)
     kinds = {b.kind for b in plan.boxes()}

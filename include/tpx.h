@@ -306,7 +306,7 @@ tpx_status tpx_get_segment(const tpx_plan_t*, uint64_t i, tpx_segment* out);
 tpx_status tpx_traffic(const tpx_plan_t*, uint64_t* out);
 
 /* DEVICE bytes tpx_execute needs in `workspace` (a header, then the plan tables: flat boxes, tile prefix
- * sums, merge segments). */
+ * sums, the segments of merge and pack tiles). */
 uint64_t   tpx_workspace_bytes(const tpx_plan_t*);
 
 /* Apply the plan (section 5.1, step 4): one kernel launch on `hip_stream` (a hipStream_t, NULL = the

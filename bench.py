@@ -200,7 +200,8 @@ def main() -> int:
         src_bufs.append(b)
     for r in range(n_dst):
         dst_bufs.append(torch.zeros(plan.buffer_bytes(1, r), dtype=torch.uint8, device="cuda"))
-    ws = torch.empty(plan.workspace_bytes(), dtype=torch.uint8, device="cuda")
+    two = TwoWorkspaces(plan.workspace_bytes())
+    ws = two.ws[0]
     src_ptrs = [b.data_ptr() for b in src_bufs]
     dst_ptrs = [b.data_ptr() for b in dst_bufs]
     stream = torch.cuda.current_stream().cuda_stream
@@ -211,12 +212,14 @@ def main() -> int:
 
     def step(ev0=None, ev1=None):
         p = tpx.tpx_plan(model, src, dst, args.opts)   # a1-a5: host planner
-        p.prepare(ws.data_ptr(), stream)            # tile table -> HBM
+        k, w, upload_stream = two.next()
+        p.prepare(w, upload_stream)                 # tile table -> HBM (waits for the copy)
         if ev0 is not None:
             ev0.record()
-        p.execute(src_ptrs, dst_ptrs, ws.data_ptr(), stream)   # a6: one launch
+        p.execute(src_ptrs, dst_ptrs, w, stream)    # a6: one launch
         if ev1 is not None:
             ev1.record()
+        two.used(k)
         return p
 
     for _ in range(args.warmup):
@@ -331,6 +334,33 @@ def main() -> int:
     }
     print(json.dumps(out), flush=True)
     return 0
+
+
+class TwoWorkspaces:
+    """The plan tables of consecutive steps go to two workspaces in turn, uploaded on a stream of their own, so that the
+    upload for step i + 1 runs while step i's kernel (which reads the other workspace) is still busy, and kernel i + 1 is
+    queued right behind kernel i.  Before a workspace is overwritten, the upload stream waits for the last kernel that
+    read it."""
+
+    def __init__(self, nbytes):
+        import torch
+        self.ws = [torch.empty(nbytes, dtype=torch.uint8, device="cuda") for _ in range(2)]
+        self.upload = torch.cuda.Stream()
+        self.done = [None, None]
+        self.turn = 0
+
+    def next(self):
+        import torch
+        k = self.turn
+        self.turn ^= 1
+        if self.done[k] is not None:
+            self.upload.wait_event(self.done[k])
+        return k, self.ws[k].data_ptr(), self.upload.cuda_stream
+
+    def used(self, k):
+        import torch
+        self.done[k] = torch.cuda.Event()
+        self.done[k].record()
 
 
 PLAN_KEYS = ("tile_bytes", "max_multicast", "share_reads", "pack_bytes")
@@ -448,19 +478,22 @@ def bench_dataset(args) -> int:
         parts.append(np.concatenate([body, G[full * B + j * b: full * B + min(tail, (j + 1) * b)]]))
     src_bufs = [torch.from_numpy(p.view(np.uint8)).cuda() for p in parts]
     dst_bufs = [torch.zeros(plan.buffer_bytes(1, j), dtype=torch.uint8, device="cuda") for j in range(D2)]
-    ws = torch.empty(plan.workspace_bytes(), dtype=torch.uint8, device="cuda")
+    two = TwoWorkspaces(plan.workspace_bytes())
+    ws = two.ws[0]
     sp, dp = [x.data_ptr() for x in src_bufs], [x.data_ptr() for x in dst_bufs]
     stream = torch.cuda.current_stream().cuda_stream
     state_bytes = stats["bytes_read"] + stats["bytes_written"]
 
     def step(e0=None, e1=None):
         p = tpx.tpx_plan_dataset(n, B, D, D2, cursors, opts=args.opts)
-        p.prepare(ws.data_ptr(), stream)
+        k, w, upload_stream = two.next()
+        p.prepare(w, upload_stream)
         if e0 is not None:
             e0.record()
-        p.execute(sp, dp, ws.data_ptr(), stream)
+        p.execute(sp, dp, w, stream)
         if e1 is not None:
             e1.record()
+        two.used(k)
         return p
 
     for _ in range(args.warmup):

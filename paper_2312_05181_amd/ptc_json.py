@@ -16,7 +16,6 @@ from __future__ import annotations
 
 import json
 from collections import namedtuple
-from typing import Iterable
 
 Block = namedtuple("Block", "tensor_id kind elem_bytes offset full_shape lo hi perm name layer path")
 

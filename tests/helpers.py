@@ -3,7 +3,6 @@ from the oracle's layout, and conversions between the oracle's manifest entries
 and the input generator's block descriptions."""
 from __future__ import annotations
 
-import numpy as np
 import torch
 
 import synth

@@ -16,7 +16,7 @@ from oracle import spec
 from oracle.spec import Model, Parallel
 from tests import gpu_util as G
 from tests import helpers as H
-from tests.test_planner import ODD, ODD_MIX, PAIRS, SMALL, SMALL_MIX, WIDE, mk, pk, plan_for
+from tests.test_planner import ODD, ODD_MIX, PAIRS, SMALL, SMALL_MIX, WIDE, plan_for
 
 pytestmark = pytest.mark.gpu
 

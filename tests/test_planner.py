@@ -421,7 +421,6 @@ def test_error_codes():
     assert st(lambda: tpx.tpx_plan(m, dict(T=1, P=2, D=1, layer_stage=(0, 1, 1)), one)) == B.TPX_ERR_INVALID_ARG
     assert st(lambda: tpx.tpx_plan_ptc([[]], [[]], src_bytes=[0, 0])) == B.TPX_ERR_INVALID_ARG
     assert st(lambda: tpx.tpx_plan_ptc([[]], [[]], src_alive=[1, 1])) == B.TPX_ERR_INVALID_ARG
-    import ctypes as C
     assert B._lib.tpx_plan(None, None, None, None, None) == B.TPX_ERR_INVALID_ARG
     assert B._lib.tpx_execute(None, None, None, None, None) == B.TPX_ERR_INVALID_ARG
     assert b"NULL" in B._lib.tpx_last_error()

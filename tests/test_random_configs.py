@@ -10,11 +10,10 @@ import torch
 import paper_2312_05181_amd as tpx
 import synth
 from oracle import reshard as oreshard
-from oracle import spec
 from oracle.spec import Model, Parallel
 from tests import helpers as H
 from tests import host_exec
-from tests.test_generic_ptc import closed_form, pack, plan_of, src_buffers
+from tests.test_generic_ptc import pack, plan_of
 from tests.test_planner import plan_for
 
 

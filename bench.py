@@ -140,9 +140,14 @@ def main() -> int:
     ap.add_argument("--ab", default=None, metavar="CFG;CFG;...",
                     help="compare settings inside ONE process on fixed buffers (differences between processes are larger than most "
                          "effects): each CFG is a comma list of key=value with keys streams, chunk, occupancy, variant (executor "
-                         "knobs), tile_bytes, max_multicast, share_reads, pack_bytes (plan options) and dst_shift_kib (all buffers of a side in one "
-                         "allocation, the destination side moved by that many KiB); prints one JSON line")
+                         "knobs), tile_bytes, max_multicast, share_reads, pack_bytes (plan options) and dst_shift_kib, rank_skew_kib (all buffers "
+                         "of a side in one allocation at 2 MiB boundaries; the destination side moved by that many KiB, rank buffer r "
+                         "by (r mod 8) times that many KiB); prints one JSON line")
     ap.add_argument("--no-probe", action="store_true")
+    ap.add_argument("--settle-s", type=float, default=4.0,
+                    help="before the warm-up steps, keep the device under load (untimed launches of the same plan) for this many "
+                         "seconds: its memory throughput steps up by about 0.8 %% after some 3.5 s of sustained load, and a "
+                         "reconfiguration interrupts a job whose GPU is already under load (0 = none)")
     ap.add_argument("--share-reads", action="store_true",
                     help="plan with the share_reads option: replicas of a group are all written from one read")
     ap.add_argument("--fill", choices=["synth", "cheap"], default="synth",
@@ -222,6 +227,7 @@ def main() -> int:
         two.used(k)
         return p
 
+    settle(args.settle_s, lambda: plan.execute(src_ptrs, dst_ptrs, ws.data_ptr(), stream))
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -336,6 +342,16 @@ def main() -> int:
     return 0
 
 
+def settle(seconds, launch):
+    """Keep the device busy with `launch` (asynchronous, queued a few deep) for about `seconds` of wall-clock time."""
+    import torch
+    t_end = time.perf_counter() + seconds
+    while seconds > 0 and time.perf_counter() < t_end:
+        for _ in range(4):
+            launch()
+        torch.cuda.synchronize()
+
+
 class TwoWorkspaces:
     """The plan tables of consecutive steps go to two workspaces in turn, uploaded on a stream of their own, so that the
     upload for step i + 1 runs while step i's kernel (which reads the other workspace) is still busy, and kernel i + 1 is
@@ -379,7 +395,7 @@ def ab_compare(args) -> int:
     cfgs = []
     for text in args.ab.split(";"):
         cfg = dict((kv.split("=")[0].strip(), int(kv.split("=")[1])) for kv in text.split(",") if kv.strip())
-        unknown = set(cfg) - set(PLAN_KEYS) - set(KNOB_DEFAULTS) - {"dst_shift_kib"}
+        unknown = set(cfg) - set(PLAN_KEYS) - set(KNOB_DEFAULTS) - {"dst_shift_kib", "rank_skew_kib"}
         if unknown:
             print(f"bench.py --ab: unknown key {sorted(unknown)[0]}", file=sys.stderr)
             return 2
@@ -403,9 +419,12 @@ def ab_compare(args) -> int:
     sp, dp = [b.data_ptr() for b in src_bufs], [b.data_ptr() for b in dst_bufs]
     stream = torch.cuda.current_stream().cuda_stream
     shifts = [cfg.get("dst_shift_kib", 0) << 10 for _, cfg in cfgs]
-    if any(shifts):
-        # placement study: all rank buffers of a side inside one allocation, each at a 2 MiB boundary, and the destination
-        # side as a whole moved by the setting's shift (a multiple of 16 bytes, as tpx_execute requires)
+    skews = [cfg.get("rank_skew_kib", 0) << 10 for _, cfg in cfgs]
+    placed = any(shifts) or any(skews)
+    if placed:
+        # placement study: all rank buffers of a side inside one allocation, each at a 2 MiB boundary, the destination
+        # side as a whole moved by the setting's shift, and rank buffer r of either side moved by (r mod 8) x the
+        # setting's skew (multiples of 16 bytes, as tpx_execute requires)
         del src_bufs, dst_bufs
         mib2 = 1 << 21
 
@@ -413,21 +432,24 @@ def ab_compare(args) -> int:
             offs, off = [], 0
             for r in range(p0.num_buffers(side)):
                 offs.append(off)
-                off = (off + p0.buffer_bytes(side, r) + mib2 - 1) // mib2 * mib2
+                off = (off + p0.buffer_bytes(side, r) + 7 * max(skews) + mib2 - 1) // mib2 * mib2     # room for the largest skew
             mem = torch.full((off + extra + mib2,), 1 + side, dtype=torch.uint8, device="cuda")
             base = (mem.data_ptr() + mib2 - 1) // mib2 * mib2
             return mem, [base + o for o in offs]
-        src_mem, sp = arena(0, 0)
+        src_mem, sp0 = arena(0, 0)
         dst_mem, dp0 = arena(1, max(shifts))
 
     def timed(plan, cfg, launches=6):
-        nonlocal dp
+        nonlocal sp, dp
         for key, default in KNOB_DEFAULTS.items():
             tpx.tpx_set_option(key, cfg.get(key, default))
-        if any(shifts):
-            if (cfg.get("dst_shift_kib", 0) << 10) % 16:
-                raise SystemExit("dst_shift_kib must give a multiple of 16 bytes")
-            dp = [q + (cfg.get("dst_shift_kib", 0) << 10) for q in dp0]
+        if placed:
+            # rank buffer r of either side starts r * rank_skew_kib past its 2 MiB boundary (r mod 8, so the skew stays small)
+            shift, skew = cfg.get("dst_shift_kib", 0) << 10, cfg.get("rank_skew_kib", 0) << 10
+            if shift % 16 or skew % 16:
+                raise SystemExit("dst_shift_kib and rank_skew_kib must give multiples of 16 bytes")
+            sp = [q + (r % 8) * skew for r, q in enumerate(sp0)]
+            dp = [q + shift + (r % 8) * skew for r, q in enumerate(dp0)]
         tpx.tpx_workspace_forget(ws.data_ptr())
         for _ in range(2):
             plan.execute(sp, dp, ws.data_ptr(), stream)
@@ -441,6 +463,9 @@ def ab_compare(args) -> int:
         st = plan.stats()
         return (st["bytes_read"] + st["bytes_written"]) / (e0.elapsed_time(e1) / launches * 1e-3) / 1e9
 
+    t_end = time.perf_counter() + args.settle_s          # device under load for a while before anything is compared
+    while time.perf_counter() < t_end:
+        timed(plans[0], cfgs[0][1])
     rounds = [[] for _ in cfgs]
     for _ in range(3):
         for i, ((_, cfg), plan) in enumerate(zip(cfgs, plans)):
@@ -496,6 +521,7 @@ def bench_dataset(args) -> int:
         two.used(k)
         return p
 
+    settle(args.settle_s, lambda: plan.execute(sp, dp, ws.data_ptr(), stream))
     for _ in range(args.warmup):
         step()
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]

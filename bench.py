@@ -413,20 +413,21 @@ def ab_compare(args) -> int:
 
     plans = [make_plan(cfg) for _, cfg in cfgs]
     p0 = plans[0]
-    src_bufs = [torch.full((max(1, p0.buffer_bytes(0, r)),), r + 1, dtype=torch.uint8, device="cuda") for r in range(p0.num_buffers(0))]
-    dst_bufs = [torch.zeros(max(1, p0.buffer_bytes(1, r)), dtype=torch.uint8, device="cuda") for r in range(p0.num_buffers(1))]
     ws = torch.empty(max(p.workspace_bytes() for p in plans), dtype=torch.uint8, device="cuda")
-    sp, dp = [b.data_ptr() for b in src_bufs], [b.data_ptr() for b in dst_bufs]
     stream = torch.cuda.current_stream().cuda_stream
     shifts = [cfg.get("dst_shift_kib", 0) << 10 for _, cfg in cfgs]
     skews = [cfg.get("rank_skew_kib", 0) << 10 for _, cfg in cfgs]
     placed = any(shifts) or any(skews)
-    if placed:
+    if not placed:
+        src_bufs = [torch.full((max(1, p0.buffer_bytes(0, r)),), r + 1, dtype=torch.uint8, device="cuda") for r in range(p0.num_buffers(0))]
+        dst_bufs = [torch.zeros(max(1, p0.buffer_bytes(1, r)), dtype=torch.uint8, device="cuda") for r in range(p0.num_buffers(1))]
+        sp, dp = [b.data_ptr() for b in src_bufs], [b.data_ptr() for b in dst_bufs]
+    else:
         # placement study: all rank buffers of a side inside one allocation, each at a 2 MiB boundary, the destination
         # side as a whole moved by the setting's shift, and rank buffer r of either side moved by (r mod 8) x the
         # setting's skew (multiples of 16 bytes, as tpx_execute requires)
-        del src_bufs, dst_bufs
         mib2 = 1 << 21
+        sp = dp = None
 
         def arena(side, extra):
             offs, off = [], 0

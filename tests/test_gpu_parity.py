@@ -418,6 +418,22 @@ def test_dataset_small(cuda, n, Bsz, D, D2, s):
     _dataset_case(n, Bsz, D, D2, s)
 
 
+def test_dataset_random(cuda):
+    """300 seeded random repartitionings: 1 to 12 replicas on either side, any global batch both divide, any step of the epoch
+    (also none consumed, all consumed, fewer samples than one batch, no samples), 8- and 16-byte entries."""
+    import math
+    import random
+    rng = random.Random(77)
+    for i in range(300):
+        D, D2 = rng.randrange(1, 13), rng.randrange(1, 13)
+        Bsz = math.lcm(D, D2) * rng.randrange(1, 9)
+        n = rng.choice([0, rng.randrange(1, Bsz + 1), rng.randrange(1, 40 * Bsz), rng.randrange(1, 3000 * Bsz)])
+        s = rng.randrange(0, -(-n // Bsz) + 1)
+        eb = rng.choice([8, 16])
+        print("dataset", i, (n, Bsz, D, D2, s, eb), flush=True)
+        _dataset_case(n, Bsz, D, D2, s, seed=i, eb=eb)
+
+
 @pytest.mark.parametrize("eb", [8, 16])
 def test_dataset_full_size(cuda, eb):
     """10^8 samples, 6 -> 4 replicas after 65,000 steps: ids (8 bytes) and (offset, length) pairs (16 bytes)."""

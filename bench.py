@@ -334,6 +334,8 @@ def main() -> int:
         "write_probe_GBps": write_probe,
         # the rate of a memory that serves the reads at the read-only rate and the writes at the write-only rate, in turn
         "read_write_mix_GBps": round(2 / (1 / read_probe + 1 / write_probe), 1) if read_probe and write_probe else None,
+        "pct_of_read_write_mix": round(100 * achieved / (2 / (1 / read_probe + 1 / write_probe)), 2) if read_probe and write_probe else None,
+        "pct_of_copy_probe": round(100 * achieved / probe, 2) if probe else None,
         "setup_s": round(setup_s, 1),
         "roofline": roofline,
         "cpu_baseline": cpu,
